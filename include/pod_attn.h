@@ -1,0 +1,205 @@
+/*
+ * pod_attn.h - C ABI of the MI355X (gfx950) hybrid-batch attention library.
+ *
+ * One call computes attention for a batch that mixes causal chunked-prefill
+ * requests (a chunk of new query tokens over its cached prefix plus itself) and
+ * single-token decode requests, all against a KV cache, with both kinds of work
+ * running at the same time on the same compute units (paper Section 4: one fused
+ * kernel; Section 4.1: each workgroup picks its operation after it has landed on
+ * a compute unit).
+ *
+ * What is computed, per request r with (q_len, kv_len), local query row i, query
+ * head h (paper Section 2.1, the attention equation and the paragraph on heads):
+ *
+ *     pos  = kv_len - q_len + i            absolute position of the query token
+ *     kvh  = h / (n_q_heads / n_kv_heads)  K/V head that serves query head h
+ *     s_j  = softmax_scale * <Q[r,i,h,:], K[r,j,kvh,:]>        j = 0 .. pos
+ *     out[r,i,h,:] = sum_j softmax_j(s) * V[r,j,kvh,:]
+ *
+ * The new tokens' K/V are already in the cache (kv_len counts them).  A decode
+ * request is the case q_len == 1.  Inputs and output are 16-bit floats; scores,
+ * the softmax and all sums are fp32 on the GPU.
+ *
+ * Conventions for every entry point:
+ *   - "host" pointers are ordinary CPU memory; "device" pointers are memory of the
+ *     HIP device that is current when the call is made.  The library never takes
+ *     ownership of a caller buffer and never frees one.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device work is asynchronous with respect to the host and ordered on `stream`.
+ *   - Every function that returns pod_status returns POD_OK or a negative code and
+ *     launches nothing when it fails; pod_attn_last_error() gives a message
+ *     (thread-local storage, valid until the same thread's next failing call).
+ *   - No CPU fallback exists: without a HIP device the compute calls fail.
+ */
+#ifndef POD_ATTN_H
+#define POD_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    POD_OK = 0,
+    POD_ERR_INVALID_ARG = -1,   /* null pointer, inconsistent sizes, bad seq_meta      */
+    POD_ERR_UNSUPPORTED = -2,   /* head_dim / dtype / group size outside what is built */
+    POD_ERR_WORKSPACE = -3,     /* workspace missing or too small                      */
+    POD_ERR_HIP = -4            /* a HIP runtime call failed                           */
+} pod_status;
+
+typedef enum { POD_F16 = 0, POD_BF16 = 1 } pod_dtype;
+
+/* How pod_attn_forward schedules the two operations. */
+typedef enum {
+    POD_MODE_FUSED = 0,         /* one launch, roles bound per workgroup at run time (Section 4.1) */
+    POD_MODE_SERIAL = 1,        /* prefill kernel, then decode kernel, one stream (Section 3.1)    */
+    POD_MODE_STREAMS = 2,       /* the same two kernels on two streams, joined (Section 3.1)       */
+    POD_MODE_PREFILL_ONLY = 3,  /* only the prefill rows of `out` are written                      */
+    POD_MODE_DECODE_ONLY = 4    /* only the decode rows of `out` are written                       */
+} pod_mode;
+
+/* Which operation a workgroup takes first on its compute unit (Section 4.1, the two policies). */
+typedef enum {
+    POD_POLICY_AUTO = 0,
+    POD_POLICY_ALTERNATE = 1,   /* 50:50 - successive workgroups of a unit alternate             */
+    POD_POLICY_PROPORTIONAL = 2 /* in the ratio of prefill to decode work of this batch          */
+} pod_policy;
+
+typedef struct {
+    int32_t n_prefill;          /* prefill requests (may be 0)                                   */
+    int32_t n_decode;           /* decode requests (may be 0)                                    */
+    int32_t n_q_heads;          /* Hq                                                            */
+    int32_t n_kv_heads;         /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16                         */
+    int32_t head_dim;           /* d: 64 or 128                                                  */
+    int32_t dtype;              /* pod_dtype of q, k, v and out                                  */
+    float   softmax_scale;      /* multiplies Q K^T; must be > 0 (1/sqrt(d) in normal use)       */
+    int32_t block_size;         /* tokens per cache block; 0 = contiguous cache                  */
+    int32_t max_blocks_per_seq; /* paged: row length of block_table                              */
+    int32_t n_cache_rows;       /* contiguous: sequences in the cache; paged: block_table rows   */
+    int32_t n_blocks;           /* paged: physical blocks in the cache                           */
+    int64_t kv_seq_stride;      /* contiguous: elements between sequences (>= max kv_len*Hkv*d)  */
+    int32_t policy;             /* pod_policy                                                    */
+    int32_t max_prefill_waves;  /* cap on prefill split-KV (Section 4.2.4): prefill work items
+                                   fill at most this many chip-wide rounds; 0 = 2                */
+    int32_t decode_chunk;       /* tokens per decode work unit (split-KV length); 0 = automatic  */
+    int32_t prefill_split_len;  /* minimum keys per prefill split; 0 = automatic                 */
+    int32_t n_compute_units;    /* 0 = ask the current device (256 on MI355X if none is present) */
+} pod_attn_params;
+
+/* Counts that describe a plan; filled by pod_attn_plan_info. */
+typedef struct {
+    int32_t n_prefill_items;    /* prefill work items (row block x K/V head x split)             */
+    int32_t n_decode_units;     /* decode work units (request x K/V head x split), one per wave  */
+    int32_t n_combine;          /* output groups that are merged from split partials             */
+    int32_t max_prefill_splits;
+    int32_t max_decode_splits;
+    int32_t decode_chunk;       /* tokens per decode unit actually chosen                        */
+    int32_t prefill_ratio;      /* roles per compute unit, prefill : decode                      */
+    int32_t decode_ratio;
+    int32_t fused_grid;         /* workgroups of the fused launch                                */
+    int32_t n_compute_units;
+    int64_t n_prefill_rows;     /* sum of q_len over prefill requests                            */
+    int64_t n_partial_rows;     /* rows of fp32 partial output held in the workspace             */
+    int64_t workspace_bytes;
+} pod_attn_plan_info;
+
+typedef struct pod_attn_plan pod_attn_plan;   /* opaque, host memory, owned by the caller */
+
+/*
+ * seq_meta: int32 [n_prefill + n_decode][4] = {q_start, q_len, kv_len, cache_row},
+ * prefill requests first.
+ *   q_start    first row of the request in prefill_q (prefill) / its row in decode_q (decode)
+ *   q_len      new query tokens (prefill: >= 1; decode: exactly 1)
+ *   kv_len     tokens visible to the request's last query, the new ones included (>= q_len)
+ *   cache_row  sequence slot (contiguous cache) or block_table row (paged cache)
+ *
+ * pod_attn_plan_create: host-only.  Validates params and seq_meta (host pointer) and
+ * splits the batch into work items, as the paper does before its launch (Section 4.1:
+ * the numbers of prefill and decode CTAs are fixed on the host): prefill row blocks with
+ * split-KV capped per Section 4.2.4, decode units of one wavefront each (Section 4.2.3),
+ * and the role ratio (Section 4.1).  On success *plan is a new object that the caller
+ * releases with pod_attn_plan_destroy.  Needs no GPU when n_compute_units is given.
+ */
+pod_status pod_attn_plan_create(const pod_attn_params *params, const int32_t *seq_meta_host,
+                                pod_attn_plan **plan);
+void       pod_attn_plan_destroy(pod_attn_plan *plan);
+pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info *info);
+
+/* Bytes of device workspace the plan needs (work tables, counters, split partials). */
+size_t     pod_attn_workspace_size(const pod_attn_plan *plan);
+
+/*
+ * Copy the plan's work tables into `workspace` (device, >= pod_attn_workspace_size bytes,
+ * 256-byte aligned) and zero its counters.  Once per batch; the workspace then serves any
+ * number of pod_attn_forward calls with this plan (one per layer in a model).  Calls that
+ * share a workspace must not overlap in time.  Returns after the copy has completed.
+ */
+pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
+ * The hybrid-batch attention call (Section 4: prefill and decode attention of one batch in
+ * one kernel; rows ordered as in Figure 3, prefill tokens first, then decode tokens).
+ *
+ * All pointers are device memory:
+ *   prefill_q   [sum q_len][Hq][d]           16-bit; may be NULL when n_prefill == 0
+ *   decode_q    [n_decode][Hq][d]            16-bit; may be NULL when n_decode == 0
+ *   k_cache,    contiguous: [n_cache_rows][max_len][Hkv][d] with kv_seq_stride elements
+ *   v_cache                 between sequences;
+ *               paged:      [n_blocks][block_size][Hkv][d]
+ *   seq_meta    device copy of the array given to pod_attn_plan_create
+ *   block_table paged: int32 [n_cache_rows][max_blocks_per_seq], entry [row][t / block_size]
+ *               is the physical block of token t (token t sits at offset t % block_size);
+ *               NULL for a contiguous cache.  Entries past a sequence's last block, cache
+ *               slots at positions >= kv_len and unreferenced blocks are never read.
+ *   out         [sum q_len + n_decode][Hq][d] 16-bit, prefill rows first, then one row per
+ *               decode request in decode_q order; rounded to nearest-even from fp32.
+ *   workspace   as prepared by pod_attn_plan_upload with this plan.
+ *
+ * The device arrays are trusted: a seq_meta that differs from the planned one, or a block
+ * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode.
+ */
+pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
+                            const void *k_cache, const void *v_cache,
+                            const int32_t *seq_meta, const int32_t *block_table,
+                            void *out,
+                            const pod_attn_plan *plan, void *workspace, size_t workspace_bytes,
+                            int32_t mode, void *stream);
+
+/*
+ * Host model of the on-device role binder (Section 4.1, the scheduling listing), for tests.
+ * `events` (host, n_events entries) is a history of one launch: a value v >= 0 means a workgroup
+ * arrives on compute unit v (any id; taken modulo 1024); a value v < 0 means the workgroup
+ * created by arrival number -v - 1 (counting arrivals from 0) has finished and leaves its unit.
+ * Each arrival takes a ticket from its unit's counter, picks prefill or decode so that the
+ * unit's resident mix stays near prefill_ratio : decode_ratio (a tie is broken by the listing's
+ * rule, ticket mod (p + d) < p means prefill), claims the next work id of that operation and
+ * switches operation if that one is exhausted.  For arrival number a, role_out[a] is 0 (prefill),
+ * 1 (decode) or -1 (nothing left) and item_out[a] the claimed id (-1 if none); both arrays hold
+ * one entry per arrival.  Returns the number of arrivals that got work, or -1 for bad arguments.
+ */
+int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items,
+                                 int32_t prefill_ratio, int32_t decode_ratio,
+                                 const int32_t *events, int32_t n_events,
+                                 int32_t *role_out, int32_t *item_out);
+
+/*
+ * Read one row of the plan's work tables (host), for tests:
+ *   prefill item: {request, kv_head, first packed row, n packed rows, kv_begin, kv_end,
+ *                  first partial row or -1, split index}
+ *   decode unit : {request, kv_head, token_begin, token_end, first partial row or -1,
+ *                  split index, 0, 0}
+ * Returns POD_ERR_INVALID_ARG when index is out of range.
+ */
+pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
+pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
+
+const char *pod_attn_last_error(void);
+const char *pod_attn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POD_ATTN_H */

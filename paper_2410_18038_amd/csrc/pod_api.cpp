@@ -1,0 +1,331 @@
+// C ABI of the library (see include/pod_attn.h).
+#include <hip/hip_runtime_api.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pod_attn.h"
+#include "pod_common.h"
+#include "pod_launch.h"
+#include "pod_planner.h"
+
+struct pod_attn_plan {
+    pod::Plan p;
+};
+
+namespace {
+
+thread_local std::string g_last_error;
+
+pod_status fail(pod_status code, const std::string &msg)
+{
+    g_last_error = msg;
+    return code;
+}
+
+pod_status fail_hip(hipError_t e, const char *what)
+{
+    return fail(POD_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+int device_cu_count()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 256; }
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return n;
+}
+
+pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void *decode_q,
+                          const void *k_cache, const void *v_cache, const int32_t *seq_meta,
+                          const int32_t *block_table, void *out, void *workspace)
+{
+    pod::KernelArgs a;
+    std::memset(&a, 0, sizeof a);
+    unsigned char *ws = (unsigned char *)workspace;
+    a.prefill_q = prefill_q; a.decode_q = decode_q; a.k_cache = k_cache; a.v_cache = v_cache;
+    a.seq_meta = seq_meta; a.block_table = block_table; a.out = out;
+    a.hdr = (pod::WsHeader *)ws;
+    a.pitems = (const pod::PrefillItem *)(ws + p.off_pitems);
+    a.dunits = (const pod::DecodeUnit *)(ws + p.off_dunits);
+    a.centries = (const pod::CombineEntry *)(ws + p.off_centries);
+    a.part_o = (float *)(ws + p.off_part_o);
+    a.part_ml = (float *)(ws + p.off_part_ml);
+    a.kv_seq_stride = p.prm.kv_seq_stride;
+    a.n_prefill = p.prm.n_prefill;
+    a.n_q_heads = p.prm.n_q_heads;
+    a.n_kv_heads = p.prm.n_kv_heads;
+    a.group = p.group;
+    a.block_size = p.prm.block_size;
+    a.max_blocks_per_seq = p.prm.max_blocks_per_seq;
+    a.bs_shift = -1;
+    if (p.prm.block_size > 0 && (p.prm.block_size & (p.prm.block_size - 1)) == 0) {
+        int s = 0;
+        while ((1 << s) < p.prm.block_size) ++s;
+        a.bs_shift = s;
+    }
+    a.n_pitems = (int)p.pitems.size();
+    a.n_dunits = (int)p.dunits.size();
+    a.n_dwgs = p.n_dwgs;
+    a.n_combine = (int)p.centries.size();
+    a.n_prefill_rows = (int)p.n_prefill_rows;
+    a.p_ratio = p.p_ratio;
+    a.d_ratio = p.d_ratio;
+    a.scale_log2 = p.prm.softmax_scale * 1.4426950408889634f;
+    return a;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pod_attn_last_error(void) { return g_last_error.c_str(); }
+const char *pod_attn_version(void) { return "pod_attn 0.1 (gfx950)"; }
+
+pod_status pod_attn_plan_create(const pod_attn_params *params, const int32_t *seq_meta_host,
+                                pod_attn_plan **plan)
+{
+    if (!params || !plan) return fail(POD_ERR_INVALID_ARG, "params or plan is null");
+    *plan = nullptr;
+    const int n_cus = params->n_compute_units > 0 ? params->n_compute_units : device_cu_count();
+    pod_attn_plan *obj = new (std::nothrow) pod_attn_plan();
+    if (!obj) return fail(POD_ERR_INVALID_ARG, "out of host memory");
+    std::string err;
+    pod_status st;
+    try {
+        st = pod::build_plan(*params, seq_meta_host, n_cus, obj->p, err);
+    } catch (const std::bad_alloc &) {
+        st = POD_ERR_INVALID_ARG;
+        err = "out of host memory";
+    }
+    if (st != POD_OK) {
+        delete obj;
+        return fail(st, err);
+    }
+    *plan = obj;
+    return POD_OK;
+}
+
+void pod_attn_plan_destroy(pod_attn_plan *plan)
+{
+    if (!plan) return;
+    for (void *&s : plan->p.side_stream)
+        if (s) { (void)hipStreamDestroy((hipStream_t)s); s = nullptr; }
+    for (void *&e : plan->p.events)
+        if (e) { (void)hipEventDestroy((hipEvent_t)e); e = nullptr; }
+    delete plan;
+}
+
+pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info *info)
+{
+    if (!plan || !info) return fail(POD_ERR_INVALID_ARG, "plan or info is null");
+    const pod::Plan &p = plan->p;
+    info->n_prefill_items = (int32_t)p.pitems.size();
+    info->n_decode_units = (int32_t)p.dunits.size();
+    info->n_combine = (int32_t)p.centries.size();
+    info->max_prefill_splits = p.max_psplits;
+    info->max_decode_splits = p.max_dsplits;
+    info->decode_chunk = p.decode_chunk;
+    info->prefill_ratio = p.p_ratio;
+    info->decode_ratio = p.d_ratio;
+    info->fused_grid = (int32_t)p.pitems.size() + p.n_dwgs;
+    info->n_compute_units = p.n_cus;
+    info->n_prefill_rows = p.n_prefill_rows;
+    info->n_partial_rows = p.n_partial_rows;
+    info->workspace_bytes = (int64_t)p.ws_bytes;
+    return POD_OK;
+}
+
+size_t pod_attn_workspace_size(const pod_attn_plan *plan) { return plan ? plan->p.ws_bytes : 0; }
+
+pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8])
+{
+    if (!plan || !out || index < 0 || index >= (int32_t)plan->p.pitems.size())
+        return fail(POD_ERR_INVALID_ARG, "prefill item index out of range");
+    const pod::PrefillItem &it = plan->p.pitems[(size_t)index];
+    const int32_t v[8] = {it.req, it.kv_head, it.row0, it.n_rows, it.kv_begin, it.kv_end, it.prow0, it.split};
+    std::memcpy(out, v, sizeof v);
+    return POD_OK;
+}
+
+pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, int32_t out[8])
+{
+    if (!plan || !out || index < 0 || index >= (int32_t)plan->p.dunits.size())
+        return fail(POD_ERR_INVALID_ARG, "decode unit index out of range");
+    const pod::DecodeUnit &u = plan->p.dunits[(size_t)index];
+    const int32_t v[8] = {u.req, u.kv_head, u.t0, u.t1, u.prow0, u.split, 0, 0};
+    std::memcpy(out, v, sizeof v);
+    return POD_OK;
+}
+
+pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size_t workspace_bytes,
+                                void *stream)
+{
+    if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
+    const pod::Plan &p = plan->p;
+    if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    unsigned char *ws = (unsigned char *)workspace;
+    hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
+    if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
+    struct Part { size_t off; const void *src; size_t bytes; };
+    const Part parts[3] = {
+        {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
+        {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
+        {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)}};
+    for (const Part &part : parts) {
+        if (part.bytes == 0) continue;
+        e = hipMemcpyAsync(ws + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return fail_hip(e, "copying plan tables");
+    }
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "waiting for plan upload");
+    return POD_OK;
+}
+
+pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const void *k_cache,
+                            const void *v_cache, const int32_t *seq_meta, const int32_t *block_table,
+                            void *out, const pod_attn_plan *plan, void *workspace,
+                            size_t workspace_bytes, int32_t mode, void *stream)
+{
+    if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
+    pod::Plan &p = const_cast<pod_attn_plan *>(plan)->p;
+    const bool paged = p.prm.block_size > 0;
+    const int n_req = p.prm.n_prefill + p.prm.n_decode;
+    if (mode < POD_MODE_FUSED || mode > POD_MODE_DECODE_ONLY) return fail(POD_ERR_INVALID_ARG, "unknown mode");
+    if (n_req == 0) return POD_OK;
+    if (!k_cache || !v_cache || !seq_meta || !out) return fail(POD_ERR_INVALID_ARG, "k_cache, v_cache, seq_meta or out is null");
+    if (p.prm.n_prefill > 0 && !prefill_q) return fail(POD_ERR_INVALID_ARG, "prefill_q is null");
+    if (p.prm.n_decode > 0 && !decode_q) return fail(POD_ERR_INVALID_ARG, "decode_q is null");
+    if (paged && !block_table) return fail(POD_ERR_INVALID_ARG, "block_table is null for a paged cache");
+    if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
+    if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+
+    pod::KernelArgs a = make_args(p, prefill_q, decode_q, k_cache, v_cache, seq_meta, block_table, out, workspace);
+    hipStream_t s = (hipStream_t)stream;
+    const int dt = p.prm.dtype, hd = p.prm.head_dim;
+    hipError_t e = hipSuccess;
+    auto go = [&](int which, const pod::KernelArgs &args, hipStream_t on) {
+        if (e == hipSuccess) e = pod::launch(which, args, dt, hd, paged, on);
+    };
+
+    // The combine pass only touches groups whose partials were produced in this call.
+    pod::KernelArgs only_p = a, only_d = a;
+    {
+        // combine entries are stored prefill groups first, then decode groups
+        int n_pc = 0;
+        for (const pod::CombineEntry &c : p.centries) n_pc += (c.kind == pod::kPrefill);
+        only_p.n_combine = n_pc;
+        only_d.centries = a.centries + n_pc;
+        only_d.n_combine = a.n_combine - n_pc;
+    }
+
+    switch (mode) {
+    case POD_MODE_FUSED:
+        go(pod::kLaunchFused, a, s);
+        go(pod::kLaunchCombine, a, s);
+        break;
+    case POD_MODE_SERIAL:
+        go(pod::kLaunchPrefill, a, s);
+        go(pod::kLaunchDecode, a, s);
+        go(pod::kLaunchCombine, a, s);
+        break;
+    case POD_MODE_PREFILL_ONLY:
+        go(pod::kLaunchPrefill, a, s);
+        go(pod::kLaunchCombine, only_p, s);
+        break;
+    case POD_MODE_DECODE_ONLY:
+        go(pod::kLaunchDecode, a, s);
+        go(pod::kLaunchCombine, only_d, s);
+        break;
+    case POD_MODE_STREAMS: {
+        for (void *&ss : p.side_stream)
+            if (!ss) {
+                hipStream_t ns;
+                hipError_t ce = hipStreamCreateWithFlags(&ns, hipStreamNonBlocking);
+                if (ce != hipSuccess) return fail_hip(ce, "creating side stream");
+                ss = ns;
+            }
+        for (void *&ev : p.events)
+            if (!ev) {
+                hipEvent_t ne;
+                hipError_t ce = hipEventCreateWithFlags(&ne, hipEventDisableTiming);
+                if (ce != hipSuccess) return fail_hip(ce, "creating event");
+                ev = ne;
+            }
+        hipStream_t s0 = (hipStream_t)p.side_stream[0], s1 = (hipStream_t)p.side_stream[1];
+        hipEvent_t fork = (hipEvent_t)p.events[0], j0 = (hipEvent_t)p.events[1], j1 = (hipEvent_t)p.events[2];
+        auto chk = [&](hipError_t x) { if (e == hipSuccess) e = x; };
+        chk(hipEventRecord(fork, s));
+        chk(hipStreamWaitEvent(s0, fork, 0));
+        chk(hipStreamWaitEvent(s1, fork, 0));
+        go(pod::kLaunchPrefill, a, s0);
+        go(pod::kLaunchDecode, a, s1);
+        chk(hipEventRecord(j0, s0));
+        chk(hipEventRecord(j1, s1));
+        chk(hipStreamWaitEvent(s, j0, 0));
+        chk(hipStreamWaitEvent(s, j1, 0));
+        go(pod::kLaunchCombine, a, s);
+        break;
+    }
+    default:
+        break;
+    }
+    if (e != hipSuccess) return fail_hip(e, "launching attention kernels");
+    return POD_OK;
+}
+
+int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items,
+                                 int32_t prefill_ratio, int32_t decode_ratio,
+                                 const int32_t *events, int32_t n_events,
+                                 int32_t *role_out, int32_t *item_out)
+{
+    if (n_events < 0 || (n_events > 0 && (!events || !role_out || !item_out))) return -1;
+    if (prefill_ratio < 0 || decode_ratio < 0 || prefill_ratio + decode_ratio <= 0) return -1;
+    std::vector<uint32_t> cu_state(pod::kCuSlots, 0u);
+    uint32_t next_item[2] = {0u, 0u};
+    const uint32_t limit[2] = {(uint32_t)std::max(n_prefill_items, 0), (uint32_t)std::max(n_decode_items, 0)};
+    std::vector<int> arrival_cu, arrival_role;
+    int32_t served = 0, n_out = 0;
+    for (int32_t ev = 0; ev < n_events; ++ev) {
+        const int32_t v = events[ev];
+        if (v < 0) {                                 // departure of arrival number -v - 1
+            const size_t who = (size_t)(-(int64_t)v - 1);
+            if (who >= arrival_cu.size() || arrival_role[who] == pod::kNone) continue;
+            cu_state[(size_t)arrival_cu[who]] -=
+                arrival_role[who] == pod::kPrefill ? pod::kRunPrefillOne : pod::kRunDecodeOne;
+            arrival_role[who] = pod::kNone;
+            continue;
+        }
+        const unsigned cu = (unsigned)v & (pod::kCuSlots - 1);
+        const uint32_t state = cu_state[cu];
+        cu_state[cu] += pod::kTicketOne;
+        int role = pod::role_for_arrival(state, prefill_ratio, decode_ratio);
+        uint32_t id = next_item[role]++;
+        if (id >= limit[role]) {
+            role ^= 1;
+            id = next_item[role]++;
+            if (id >= limit[role]) role = pod::kNone;
+        }
+        if (role != pod::kNone) {
+            cu_state[cu] += role == pod::kPrefill ? pod::kRunPrefillOne : pod::kRunDecodeOne;
+            ++served;
+        }
+        role_out[n_out] = role;
+        item_out[n_out] = role == pod::kNone ? -1 : (int32_t)id;
+        ++n_out;
+        arrival_cu.push_back((int)cu);
+        arrival_role.push_back(role);
+    }
+    return served;
+}
+
+}  // extern "C"

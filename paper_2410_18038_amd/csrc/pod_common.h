@@ -1,0 +1,100 @@
+// Structures shared by the host planner and the gfx950 kernels.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define POD_HD __host__ __device__
+#else
+#define POD_HD
+#endif
+
+namespace pod {
+
+constexpr int kWaveSize = 64;
+constexpr int kWgThreads = 256;            // 4 wavefronts per workgroup, one per SIMD
+constexpr int kWavesPerWg = 4;
+constexpr int kPrefillRows = 128;          // packed (token, head-in-group) query rows per prefill item
+constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill step
+constexpr int kDecodeStep = 32;            // keys per decode step of one wavefront
+constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
+constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc << 6 | se << 4 | cu) < 1024
+
+enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
+
+// One prefill work item: a block of packed query rows of one K/V head over a key range.
+// Packed row R of a request stands for token R / group, query head kv_head * group + R % group,
+// so that the heads sharing a K/V head also share each staged K/V tile (Section 4.2.1 notes the
+// query tile grows by the group size under grouped-query attention).
+struct PrefillItem {
+    int32_t req, kv_head, row0, n_rows;
+    int32_t kv_begin, kv_end;              // keys [kv_begin, kv_end); causal limit applied inside
+    int32_t prow0;                         // first partial row, or -1 when the item writes `out`
+    int32_t split;
+};
+
+// One decode work unit: all query heads of one K/V head of one request over a token range.
+// One wavefront runs it (the "virtual CTA" of Section 4.2.3).
+struct DecodeUnit {
+    int32_t req, kv_head, t0, t1;
+    int32_t prow0;                         // first partial row (group rows), or -1
+    int32_t split, pad0, pad1;
+};
+
+// One group of output rows merged from split partials.
+struct CombineEntry {
+    int32_t kind;                          // kPrefill or kDecode
+    int32_t req, kv_head, row0, n_rows;
+    int32_t n_splits, prow0, split_stride; // partial row of split s, row r: prow0 + s*split_stride + r
+};
+
+// Counters at the head of the device workspace.  All zero between launches: the last
+// workgroup of a fused launch clears them.
+struct WsHeader {
+    // Per compute unit: bits 0-9 resident prefill workgroups, bits 10-19 resident decode
+    // workgroups, bits 20-31 arrivals so far (the ticket of Section 4.1's listing).
+    uint32_t cu_state[kCuSlots];
+    uint32_t next_item[2];                 // next work id per role
+    uint32_t done;                         // workgroups that have finished
+    uint32_t pad[61];
+};
+
+constexpr uint32_t kRunPrefillOne = 1u;
+constexpr uint32_t kRunDecodeOne = 1u << 10;
+constexpr uint32_t kTicketOne = 1u << 20;
+
+// Which operation an arriving workgroup should start, given the snapshot of its unit's state.
+// Keeps resident prefill : decode workgroups near p : d; a tie falls back to the ticket rule
+// of Section 4.1 (ticket mod (p + d) < p means prefill).
+POD_HD inline int role_for_arrival(uint32_t state, int p, int d)
+{
+    const int run_p = (int)(state & 1023u);
+    const int run_d = (int)((state >> 10) & 1023u);
+    const int ticket = (int)(state >> 20);
+    const int lhs = run_p * d, rhs = run_d * p;
+    if (lhs < rhs) return kPrefill;
+    if (lhs > rhs) return kDecode;
+    return (ticket % (p + d)) < p ? kPrefill : kDecode;
+}
+
+// Everything a kernel needs; passed by value.
+struct KernelArgs {
+    const void *prefill_q, *decode_q, *k_cache, *v_cache;
+    const int32_t *seq_meta, *block_table;
+    void *out;
+    const PrefillItem *pitems;
+    const DecodeUnit *dunits;
+    const CombineEntry *centries;
+    float *part_o;                         // [n_partial_rows][d]  un-normalised fp32 output
+    float *part_ml;                        // [n_partial_rows][2]  running max (log2 domain), weight sum
+    WsHeader *hdr;
+    int64_t kv_seq_stride;
+    int32_t n_prefill, n_q_heads, n_kv_heads, group;
+    int32_t block_size, max_blocks_per_seq;
+    int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1
+    int32_t n_pitems, n_dunits, n_dwgs, n_combine;
+    int32_t n_prefill_rows;
+    int32_t p_ratio, d_ratio;
+    float scale_log2;                      // softmax_scale * log2(e)
+};
+
+}  // namespace pod

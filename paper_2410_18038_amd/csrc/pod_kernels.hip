@@ -1,0 +1,678 @@
+// gfx950 kernels for hybrid-batch attention: the prefill path (MFMA, LDS-staged K/V tiles,
+// online softmax), the decode path (one wavefront per unit, coalesced K/V streaming), the
+// split-KV combine, and the fused kernel whose workgroups bind their operation at run time
+// from the compute unit they landed on (paper Section 4.1).
+//
+// Both paths compute S^T = K Q^T rather than S, so that every lane owns one query row:
+// the MFMA result then already has the register layout the second product (O^T = V^T P^T)
+// wants for its P operand, and the running max and sum of a row are per-lane scalars.
+#include <hip/hip_runtime.h>
+
+#include "pod_common.h"
+#include "pod_launch.h"
+
+namespace pod {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+#define POD_LDS __attribute__((address_space(3)))
+
+template <int DT> struct Num;
+template <> struct Num<0> {   // IEEE binary16
+    using v8 = f16x8;
+    using v4 = f16x4;
+    using elem = _Float16;
+    static __device__ __forceinline__ f32x16 mfma32(v8 a, v8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4 mfma16(v8 a, v8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Num<1> {   // bfloat16
+    using v8 = bf16x8;
+    using v4 = bf16x4;
+    using elem = __bf16;
+    static __device__ __forceinline__ f32x16 mfma32(v8 a, v8 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4 mfma16(v8 a, v8 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// LDS transpose read: within each group of 16 lanes, lane n receives element n of the four
+// 32-byte rows formed by the 8-byte pieces that lanes 4r..4r+3 point at (r = 0..3).
+__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *p)
+{
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((POD_LDS s16x4 *)p);
+}
+
+// Element offset (head 0, channel 0) of token t of a cache row.
+template <bool PAGED>
+__device__ __forceinline__ int64_t token_offset(const KernelArgs &a, int cache_row, int t, int token_elems)
+{
+    if constexpr (PAGED) {
+        int bi, off;
+        if (a.bs_shift >= 0) { bi = t >> a.bs_shift; off = t & (a.block_size - 1); }
+        else { bi = t / a.block_size; off = t - bi * a.block_size; }
+        const int blk = a.block_table[(int64_t)cache_row * a.max_blocks_per_seq + bi];
+        return ((int64_t)blk * a.block_size + off) * token_elems;
+    } else {
+        return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
+    }
+}
+
+// Orders LDS traffic among the lanes of one wavefront.  A wavefront's LDS instructions execute in
+// program order, so no hardware wait is needed; this only stops the compiler from moving a
+// lane's LDS access across the point where other lanes' data is exchanged.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ u32x4 load16(const void *p) { return *(const u32x4 *)p; }
+
+// ------------------------------------------------------------------------------------------
+// Prefill path (Sections 2.1 and 4.3: the prefill operation as a device function that takes
+// its work id as a parameter).  One workgroup = 4 wavefronts x 32 packed query rows; K/V tiles
+// of 64 keys are staged through LDS once and read by all four wavefronts.
+// ------------------------------------------------------------------------------------------
+template <int D> struct PrefillLds {
+    static constexpr int kKStride = D * 2 + 16;    // bytes per K row: 4-bank skew between keys
+    static constexpr int kVStride = D * 2 + 64;    // bytes per V row: 16-bank skew for transpose reads
+    static constexpr int kKBytes = kPrefillKvTile * kKStride;
+    static constexpr int kVBytes = kPrefillKvTile * kVStride;
+    static constexpr int kBytes = kKBytes + kVBytes;
+};
+
+template <int DT, int D, bool PAGED>
+__device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const PrefillItem it,
+                                                 unsigned char *smem)
+{
+    using N = Num<DT>;
+    using v8 = typename N::v8;
+    using L = PrefillLds<D>;
+    constexpr int KS = D / 16;                     // 16-channel slices of the QK^T contraction
+    constexpr int MB = D / 32;                     // 32-channel blocks of the output
+    constexpr int CH = D / 8;                      // 16-byte chunks per K/V row
+    constexpr int ROWS_PER_PASS = kWgThreads / CH;
+    constexpr int NPASS = kPrefillKvTile / ROWS_PER_PASS;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n32 = lane & 31;                     // query column owned by this lane
+    const int h = lane >> 5;                       // which half of the contraction slots
+    const int i16 = lane & 15;
+    const int b16 = (lane >> 4) & 1;
+
+    const int32_t *meta = a.seq_meta + 4 * it.req;
+    const int q_start = meta[0], q_len = meta[1], kv_len = meta[2], cache_row = meta[3];
+    const int prefix = kv_len - q_len;
+    const int group = a.group;
+    const int token_elems = a.n_kv_heads * D;
+    const int rows_total = q_len * group;
+
+    // This lane's query row.
+    const int R = it.row0 + wave * 32 + n32;
+    const bool row_ok = R < rows_total && (wave * 32 + n32) < it.n_rows;
+    const int tok = R / group;
+    const int hq = it.kv_head * group + (R - tok * group);
+    const int pos = row_ok ? prefix + tok : 0x7fffffff;    // last visible key
+    // Causal limits of this wavefront (rows are ordered by token).
+    const int w_first = it.row0 + wave * 32;
+    const int w_last = min(it.row0 + it.n_rows, it.row0 + wave * 32 + 32) - 1;
+    const bool wave_has_rows = w_first < it.row0 + it.n_rows;
+    const int wave_minpos = prefix + w_first / group;
+    const int wave_maxpos = wave_has_rows ? prefix + w_last / group : -1;
+
+    v8 q[KS];
+    {
+        const typename N::elem *qp = (const typename N::elem *)a.prefill_q +
+            ((int64_t)(q_start + tok) * a.n_q_heads + hq) * D + h * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (row_ok) raw = load16(qp + ks * 16);
+            q[ks] = __builtin_bit_cast(v8, raw);
+        }
+    }
+
+    f32x16 o[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
+    float m_run = neg_inf(), l_run = 0.f;
+    const float c = a.scale_log2;
+
+    const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * D;
+    const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * D;
+    unsigned char *lds_k = smem;
+    unsigned char *lds_v = smem + L::kKBytes;
+    const int ld_row = tid / CH, ld_chunk = tid % CH;
+
+    u32x4 kreg[NPASS], vreg[NPASS];
+    auto issue_loads = [&](int j0) {
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int t = j0 + p * ROWS_PER_PASS + ld_row;
+            u32x4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
+            if (t < it.kv_end) {
+                const int64_t off = token_offset<PAGED>(a, cache_row, t, token_elems) + ld_chunk * 8;
+                kz = load16(kc + off);
+                vz = load16(vc + off);
+            }
+            kreg[p] = kz;
+            vreg[p] = vz;
+        }
+    };
+
+    const int n_tiles = (it.kv_end - it.kv_begin + kPrefillKvTile - 1) / kPrefillKvTile;
+    if (n_tiles > 0) issue_loads(it.kv_begin);
+
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        const int j0 = it.kv_begin + jt * kPrefillKvTile;
+        __syncthreads();                           // previous tile fully consumed
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int row = p * ROWS_PER_PASS + ld_row;
+            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = kreg[p];
+            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = vreg[p];
+        }
+        __syncthreads();
+        if (jt + 1 < n_tiles) issue_loads(j0 + kPrefillKvTile);
+        if (j0 > wave_maxpos) continue;            // nothing visible to this wavefront
+
+        // S^T = K Q^T : rows = keys of the tile, columns = this wavefront's query rows.
+        f32x16 s[2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[tb][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const v8 kk = *(const v8 *)(lds_k + (tb * 32 + n32) * L::kKStride + (ks * 16 + h * 8) * 2);
+                s[tb] = N::mfma32(kk, q[ks], s[tb]);
+            }
+        }
+        // register r of block tb holds key j0 + tb*32 + 8*(r/4) + 4*h + r%4
+        const bool need_mask = (j0 + kPrefillKvTile - 1 > wave_minpos) || (j0 + kPrefillKvTile > it.kv_end);
+        if (need_mask) {
+            const int lim = min(pos, it.kv_end - 1);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = j0 + tb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    if (key > lim) s[tb][r] = neg_inf();
+                }
+        }
+        float mx = neg_inf();
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[tb][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * c);
+        const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        v8 pk[2][2];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = fast_exp2(__builtin_fmaf(s[tb][r], c, -m_use));
+                psum += p;
+                pk[tb][r >> 3][r & 7] = (typename N::elem)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+
+        // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int key0 = tb * 32 + 16 * u + 4 * h;
+                    const unsigned char *vp = lds_v + (key0 + (i16 >> 2)) * L::kVStride +
+                                              (mb * 32 + b16 * 16 + (i16 & 3) * 4) * 2;
+                    const s16x4 lo = lds_read_tr(vp);
+                    const s16x4 hi = lds_read_tr(vp + 8 * L::kVStride);
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[mb] = N::mfma32(__builtin_bit_cast(v8, both), pk[tb][u], o[mb]);
+                }
+        }
+    }
+
+    // Epilogue.  o[mb][r] is channel mb*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    if (it.prow0 < 0) {
+        if (row_ok) {
+            const float inv = 1.f / l_tot;
+            typename N::elem *op = (typename N::elem *)a.out +
+                ((int64_t)(q_start + tok) * a.n_q_heads + hq) * D;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int rq = 0; rq < 4; ++rq) {
+                    typename N::v4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (typename N::elem)(o[mb][rq * 4 + e] * inv);
+                    *(typename N::v4 *)(op + mb * 32 + 8 * rq + 4 * h) = w;
+                }
+        }
+    } else {
+        const int64_t prow = (int64_t)it.prow0 + wave * 32 + n32;
+        float *po = a.part_o + prow * D;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                f32x4 w = {o[mb][rq * 4 + 0], o[mb][rq * 4 + 1], o[mb][rq * 4 + 2], o[mb][rq * 4 + 3]};
+                *(f32x4 *)(po + mb * 32 + 8 * rq + 4 * h) = w;
+            }
+        if (h == 0) {
+            a.part_ml[prow * 2 + 0] = m_run;
+            a.part_ml[prow * 2 + 1] = l_tot;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode path (Section 4.2.3: a decode workgroup is cut into one-wavefront virtual units, so
+// no workgroup barrier is used here).  A unit streams its K and V rows once, with fully
+// coalesced 16-byte loads, through a wavefront-private LDS region that only serves to turn the
+// rows into MFMA operands; the query heads of the group are the (zero padded) 16 columns, so
+// the matrix unit is busy for a few percent of the time (Section 4.2.1).
+// ------------------------------------------------------------------------------------------
+template <int D> struct DecodeLds {
+    static constexpr int kKStride = D * 2 + 16;
+    static constexpr int kVStride = D * 2 + 32;
+    static constexpr int kKBytes = kDecodeStep * kKStride;
+    static constexpr int kVBytes = kDecodeStep * kVStride;
+    static constexpr int kBytesPerWave = kKBytes + kVBytes;
+    static constexpr int kBytes = kBytesPerWave * kWavesPerWg;
+};
+
+template <int DT, int D, bool PAGED>
+__device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const DecodeUnit u,
+                                                unsigned char *smem_wave)
+{
+    using N = Num<DT>;
+    using v8 = typename N::v8;
+    using L = DecodeLds<D>;
+    constexpr int KS = D / 32;                     // 32-channel slices of the QK^T contraction
+    constexpr int MB = D / 16;                     // 16-channel blocks of the output
+    constexpr int CH = D / 8;                      // 16-byte chunks per row
+    constexpr int RPI = kWaveSize / CH;            // rows per load instruction
+    constexpr int NLD = kDecodeStep / RPI;         // load instructions per step, for K and for V
+
+    const int lane = threadIdx.x & 63;
+    const int n16 = lane & 15;                     // query column (head within the group)
+    const int b4 = lane >> 4;
+
+    const int32_t *meta = a.seq_meta + 4 * u.req;
+    const int q_start = meta[0], cache_row = meta[3];
+    const int group = a.group;
+    const int token_elems = a.n_kv_heads * D;
+    const bool col_ok = n16 < group;
+    const int hq = u.kv_head * group + n16;
+
+    v8 q[KS];
+    {
+        const typename N::elem *qp = (const typename N::elem *)a.decode_q +
+            ((int64_t)q_start * a.n_q_heads + hq) * D + b4 * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 raw = {0u, 0u, 0u, 0u};
+            if (col_ok) raw = load16(qp + ks * 32);
+            q[ks] = __builtin_bit_cast(v8, raw);
+        }
+    }
+
+    f32x4 o[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = neg_inf(), l_run = 0.f;
+    const float c = a.scale_log2;
+
+    const typename N::elem *kc = (const typename N::elem *)a.k_cache + u.kv_head * D;
+    const typename N::elem *vc = (const typename N::elem *)a.v_cache + u.kv_head * D;
+    unsigned char *lds_k = smem_wave;
+    unsigned char *lds_v = smem_wave + L::kKBytes;
+    const int ld_row = lane / CH, ld_chunk = lane % CH;
+
+    struct Stage { u32x4 k[NLD], v[NLD]; };
+    auto issue = [&](Stage &st, int t_base) {
+#pragma unroll
+        for (int p = 0; p < NLD; ++p) {
+            const int t = t_base + p * RPI + ld_row;
+            u32x4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
+            if (t < u.t1) {
+                const int64_t off = token_offset<PAGED>(a, cache_row, t, token_elems) + ld_chunk * 8;
+                kz = load16(kc + off);
+                vz = load16(vc + off);
+            }
+            st.k[p] = kz;
+            st.v[p] = vz;
+        }
+    };
+    auto consume = [&](const Stage &st, int t_base) {
+#pragma unroll
+        for (int p = 0; p < NLD; ++p) {
+            const int row = p * RPI + ld_row;
+            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = st.k[p];
+            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = st.v[p];
+        }
+        wave_lds_sync();                           // rows written by some lanes are read by others
+        // S^T tiles of 16 keys: register r of tile tt holds key t_base + tt*16 + 4*b4 + r.
+        f32x4 s[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+            s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const v8 kk = *(const v8 *)(lds_k + (tt * 16 + n16) * L::kKStride + (ks * 32 + b4 * 8) * 2);
+                s[tt] = N::mfma16(kk, q[ks], s[tt]);
+            }
+        }
+        if (t_base + kDecodeStep > u.t1) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (t_base + tt * 16 + 4 * b4 + r >= u.t1) s[tt][r] = neg_inf();
+        }
+        float mx = neg_inf();
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[tt][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx * c);
+        const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
+        const float alpha = fast_exp2(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        v8 pk;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = fast_exp2(__builtin_fmaf(s[tt][r], c, -m_use));
+                psum += p;
+                pk[tt * 4 + r] = (typename N::elem)p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            const unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
+                                      (mb * 16 + (n16 & 3) * 4) * 2;
+            const s16x4 lo = lds_read_tr(vp);
+            const s16x4 hi = lds_read_tr(vp + 16 * L::kVStride);
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            o[mb] = o[mb] * alpha;
+            o[mb] = N::mfma16(__builtin_bit_cast(v8, both), pk, o[mb]);
+        }
+        wave_lds_sync();                           // all reads issued before the next step overwrites
+    };
+
+    const int n_steps = (u.t1 - u.t0 + kDecodeStep - 1) / kDecodeStep;
+    Stage sa, sb;
+    if (n_steps > 0) issue(sa, u.t0);
+    for (int st = 0; st < n_steps; st += 2) {
+        const int t_base = u.t0 + st * kDecodeStep;
+        if (st + 1 < n_steps) issue(sb, t_base + kDecodeStep);
+        consume(sa, t_base);
+        if (st + 1 < n_steps) {
+            if (st + 2 < n_steps) issue(sa, t_base + 2 * kDecodeStep);
+            consume(sb, t_base + kDecodeStep);
+        }
+    }
+
+    // o[mb][r] is channel mb*16 + 4*b4 + r of query column n16.
+    float l_tot = l_run + __shfl_xor(l_run, 16);
+    l_tot += __shfl_xor(l_tot, 32);
+    if (!col_ok) return;
+    if (u.prow0 < 0) {
+        const float inv = 1.f / l_tot;
+        typename N::elem *op = (typename N::elem *)a.out +
+            ((int64_t)(a.n_prefill_rows + q_start) * a.n_q_heads + hq) * D;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) {
+            typename N::v4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (typename N::elem)(o[mb][e] * inv);
+            *(typename N::v4 *)(op + mb * 16 + 4 * b4) = w;
+        }
+    } else {
+        const int64_t prow = (int64_t)u.prow0 + n16;
+        float *po = a.part_o + prow * D;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) *(f32x4 *)(po + mb * 16 + 4 * b4) = o[mb];
+        if (b4 == 0) {
+            a.part_ml[prow * 2 + 0] = m_run;
+            a.part_ml[prow * 2 + 1] = l_tot;
+        }
+    }
+}
+
+template <int D> struct FusedLds {
+    static constexpr int kBytes = PrefillLds<D>::kBytes > DecodeLds<D>::kBytes ? PrefillLds<D>::kBytes
+                                                                               : DecodeLds<D>::kBytes;
+};
+
+// ------------------------------------------------------------------------------------------
+// Stand-alone kernels: the in-house serial and two-stream baselines (Section 3.1).
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, bool PAGED>
+__global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[PrefillLds<D>::kBytes];
+    prefill_item_run<DT, D, PAGED>(a, a.pitems[blockIdx.x], smem);
+}
+
+template <int DT, int D, bool PAGED>
+__global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[DecodeLds<D>::kBytes];
+    const int wave = threadIdx.x >> 6;
+    const int unit = blockIdx.x * kWavesPerWg + wave;
+    if (unit < a.n_dunits)
+        decode_unit_run<DT, D, PAGED>(a, a.dunits[unit], smem + wave * DecodeLds<D>::kBytesPerWave);
+}
+
+// ------------------------------------------------------------------------------------------
+// Fused kernel: n_pitems + n_dwgs workgroups; each binds its operation after it has been
+// placed on a compute unit (Section 4.1).  The leader reads the hardware unit id, takes a
+// ticket from that unit's counter, chooses the operation that keeps the unit's resident mix
+// near the prefill:decode ratio, claims the next work id of that operation and switches
+// operation when it is exhausted.  The sum of work ids equals the grid size, so every
+// workgroup ends up with exactly one item.
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, bool PAGED>
+__global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[FusedLds<D>::kBytes];
+    __shared__ int bind[4];
+    WsHeader *hdr = a.hdr;
+    if (threadIdx.x == 0) {
+        const unsigned cu = __smid() & (kCuSlots - 1);
+        const uint32_t state = atomicAdd(&hdr->cu_state[cu], kTicketOne);
+        int role = role_for_arrival(state, a.p_ratio, a.d_ratio);
+        uint32_t id = atomicAdd(&hdr->next_item[role], 1u);
+        if (id >= (uint32_t)(role == kPrefill ? a.n_pitems : a.n_dwgs)) {
+            role ^= 1;
+            id = atomicAdd(&hdr->next_item[role], 1u);
+            if (id >= (uint32_t)(role == kPrefill ? a.n_pitems : a.n_dwgs)) role = kNone;
+        }
+        if (role != kNone)
+            atomicAdd(&hdr->cu_state[cu], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
+        bind[0] = role;
+        bind[1] = (int)id;
+        bind[2] = (int)cu;
+    }
+    __syncthreads();
+    const int role = bind[0];
+    const int id = bind[1];
+    if (role == kPrefill) {
+        prefill_item_run<DT, D, PAGED>(a, a.pitems[id], smem);
+    } else if (role == kDecode) {
+        const int wave = threadIdx.x >> 6;
+        const int unit = id * kWavesPerWg + wave;
+        if (unit < a.n_dunits)
+            decode_unit_run<DT, D, PAGED>(a, a.dunits[unit], smem + wave * DecodeLds<D>::kBytesPerWave);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (role != kNone)
+            atomicSub(&hdr->cu_state[bind[2]], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
+        __threadfence();
+        const uint32_t done = atomicAdd(&hdr->done, 1u);
+        bind[3] = (done == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (bind[3]) {                                  // last workgroup: leave the counters at zero
+        for (int i = threadIdx.x; i < kCuSlots; i += kWgThreads) hdr->cu_state[i] = 0u;
+        if (threadIdx.x == 0) {
+            hdr->next_item[0] = 0u;
+            hdr->next_item[1] = 0u;
+            hdr->done = 0u;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Combine: merge split-KV partials.  With running maxima m_s (log2 domain), weight sums l_s and
+// un-normalised outputs O_s:  M = max m_s,  out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+// ------------------------------------------------------------------------------------------
+template <int DT, int D>
+__global__ __launch_bounds__(kWgThreads) void combine_kernel(KernelArgs a)
+{
+    using N = Num<DT>;
+    constexpr int TPR = D / 4;                      // threads per row, 4 channels each
+    constexpr int RPP = kWgThreads / TPR;           // rows per pass
+    const CombineEntry e = a.centries[blockIdx.x];
+    const int32_t *meta = a.seq_meta + 4 * e.req;
+    const int q_start = meta[0], q_len = meta[1];
+    const int group = a.group;
+    const int sub = threadIdx.x % TPR;
+    for (int r = threadIdx.x / TPR; r < e.n_rows; r += RPP) {
+        int64_t out_row;
+        int hq;
+        if (e.kind == kPrefill) {
+            const int R = e.row0 + r;
+            const int tok = R / group;
+            if (tok >= q_len) continue;
+            hq = e.kv_head * group + (R - tok * group);
+            out_row = q_start + tok;
+        } else {
+            hq = e.kv_head * group + r;
+            out_row = (int64_t)a.n_prefill_rows + q_start;
+        }
+        float M = neg_inf();
+        for (int s = 0; s < e.n_splits; ++s)
+            M = fmaxf(M, a.part_ml[((int64_t)e.prow0 + (int64_t)s * e.split_stride + r) * 2]);
+        float lsum = 0.f;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < e.n_splits; ++s) {
+            const int64_t prow = (int64_t)e.prow0 + (int64_t)s * e.split_stride + r;
+            const float ms = a.part_ml[prow * 2];
+            if (ms == neg_inf()) continue;          // a split that saw no key of this row
+            const float w = fast_exp2(ms - M);
+            lsum += a.part_ml[prow * 2 + 1] * w;
+            const f32x4 v = *(const f32x4 *)(a.part_o + prow * D + sub * 4);
+            acc += v * w;
+        }
+        const float inv = 1.f / lsum;
+        typename N::v4 w4;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w4[i] = (typename N::elem)(acc[i] * inv);
+        *(typename N::v4 *)((typename N::elem *)a.out + (out_row * a.n_q_heads + hq) * D + sub * 4) = w4;
+    }
+}
+
+__global__ void clear_header_kernel(WsHeader *hdr)
+{
+    uint32_t *p = (uint32_t *)hdr;
+    for (int i = threadIdx.x + blockIdx.x * blockDim.x; i < (int)(sizeof(WsHeader) / 4);
+         i += blockDim.x * gridDim.x)
+        p[i] = 0u;
+}
+
+// ------------------------------------------------------------------------------------------
+// Host-side launchers.
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, bool PAGED>
+static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t stream)
+{
+    switch (which) {
+    case kLaunchPrefill:
+        if (a.n_pitems > 0)
+            prefill_kernel<DT, D, PAGED><<<dim3(a.n_pitems), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    case kLaunchDecode:
+        if (a.n_dwgs > 0)
+            decode_kernel<DT, D, PAGED><<<dim3(a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    case kLaunchFused:
+        if (a.n_pitems + a.n_dwgs > 0)
+            fused_kernel<DT, D, PAGED><<<dim3(a.n_pitems + a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    case kLaunchCombine:
+        if (a.n_combine > 0)
+            combine_kernel<DT, D><<<dim3(a.n_combine), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    default:
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int DT, int D>
+static hipError_t launch_layout(int which, const KernelArgs &a, bool paged, hipStream_t stream)
+{
+    return paged ? launch_variant<DT, D, true>(which, a, stream)
+                 : launch_variant<DT, D, false>(which, a, stream);
+}
+
+hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
+{
+    if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, paged, stream);
+    if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, paged, stream);
+    if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, paged, stream);
+    if (dtype == 1 && head_dim == 64) return launch_layout<1, 64>(which, a, paged, stream);
+    return hipErrorInvalidValue;
+}
+
+hipError_t clear_header(WsHeader *hdr, hipStream_t stream)
+{
+    clear_header_kernel<<<dim3(1), dim3(256), 0, stream>>>(hdr);
+    return hipGetLastError();
+}
+
+}  // namespace pod

@@ -1,0 +1,235 @@
+// Host planner: validates a hybrid batch and cuts it into work items (paper Section 4.1: the
+// numbers of prefill and decode workgroups are fixed on the host before the launch).
+#include "pod_planner.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <numeric>
+
+namespace pod {
+
+namespace {
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+int round_up(int a, int b) { return ceil_div(a, b) * b; }
+
+std::string fmt(const char *f, long long a = 0, long long b = 0, long long c = 0)
+{
+    char buf[256];
+    std::snprintf(buf, sizeof buf, f, a, b, c);
+    return buf;
+}
+
+}  // namespace
+
+void role_ratio(int policy, int n_prefill_wgs, int n_decode_wgs, int &p, int &d)
+{
+    if (n_prefill_wgs <= 0 && n_decode_wgs <= 0) { p = 1; d = 1; return; }
+    if (n_prefill_wgs <= 0) { p = 0; d = 1; return; }
+    if (n_decode_wgs <= 0) { p = 1; d = 0; return; }
+    if (policy == POD_POLICY_ALTERNATE) { p = 1; d = 1; return; }
+    // Proportional (Section 4.1; Section 5.4.2 gives 50 prefill + 100 decode -> 1 : 2).
+    const int kMaxSide = 8;
+    if (n_decode_wgs >= n_prefill_wgs) {
+        p = 1;
+        d = std::min(kMaxSide, (int)std::lround((double)n_decode_wgs / n_prefill_wgs));
+    } else {
+        d = 1;
+        p = std::min(kMaxSide, (int)std::lround((double)n_prefill_wgs / n_decode_wgs));
+    }
+    p = std::max(p, 1);
+    d = std::max(d, 1);
+}
+
+pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n_cus, Plan &plan,
+                      std::string &err)
+{
+    // ---- parameters --------------------------------------------------------------------
+    if (prm.n_prefill < 0 || prm.n_decode < 0) { err = "negative request count"; return POD_ERR_INVALID_ARG; }
+    if (prm.n_q_heads <= 0 || prm.n_kv_heads <= 0 || prm.n_q_heads % prm.n_kv_heads != 0) {
+        err = "n_q_heads must be a positive multiple of n_kv_heads";
+        return POD_ERR_INVALID_ARG;
+    }
+    const int group = prm.n_q_heads / prm.n_kv_heads;
+    if (group > kMaxGroup) { err = "more than 16 query heads per K/V head"; return POD_ERR_UNSUPPORTED; }
+    if (prm.head_dim != 64 && prm.head_dim != 128) { err = "head_dim must be 64 or 128"; return POD_ERR_UNSUPPORTED; }
+    if (prm.dtype != POD_F16 && prm.dtype != POD_BF16) { err = "dtype must be POD_F16 or POD_BF16"; return POD_ERR_UNSUPPORTED; }
+    if (!(prm.softmax_scale > 0.f) || !std::isfinite(prm.softmax_scale)) {
+        err = "softmax_scale must be positive and finite";
+        return POD_ERR_INVALID_ARG;
+    }
+    if (prm.block_size < 0) { err = "negative block_size"; return POD_ERR_INVALID_ARG; }
+    if (prm.n_cache_rows <= 0) { err = "n_cache_rows must be positive"; return POD_ERR_INVALID_ARG; }
+    const bool paged = prm.block_size > 0;
+    if (paged && (prm.max_blocks_per_seq <= 0 || prm.n_blocks <= 0)) {
+        err = "paged cache needs max_blocks_per_seq and n_blocks";
+        return POD_ERR_INVALID_ARG;
+    }
+    if (!paged && prm.kv_seq_stride <= 0) { err = "contiguous cache needs kv_seq_stride"; return POD_ERR_INVALID_ARG; }
+    if (prm.policy < POD_POLICY_AUTO || prm.policy > POD_POLICY_PROPORTIONAL) { err = "unknown policy"; return POD_ERR_INVALID_ARG; }
+    if (prm.max_prefill_waves < 0 || prm.decode_chunk < 0 || prm.prefill_split_len < 0) {
+        err = "negative tuning parameter";
+        return POD_ERR_INVALID_ARG;
+    }
+    const int n_req = prm.n_prefill + prm.n_decode;
+    if (n_req > 0 && seq_meta == nullptr) { err = "seq_meta is null"; return POD_ERR_INVALID_ARG; }
+    if (n_cus <= 0) { err = "n_compute_units must be positive"; return POD_ERR_INVALID_ARG; }
+
+    // ---- requests ----------------------------------------------------------------------
+    const int64_t token_elems = (int64_t)prm.n_kv_heads * prm.head_dim;
+    std::vector<std::pair<int, int>> spans;         // prefill (q_start, q_len)
+    std::vector<char> decode_row_used((size_t)prm.n_decode, 0);
+    int64_t n_prefill_rows = 0;
+    for (int r = 0; r < n_req; ++r) {
+        const int32_t *m = seq_meta + 4 * r;
+        const int q_start = m[0], q_len = m[1], kv_len = m[2], row = m[3];
+        if (q_len < 1) { err = fmt("request %lld: q_len must be >= 1", r); return POD_ERR_INVALID_ARG; }
+        if (kv_len < q_len) { err = fmt("request %lld: kv_len %lld < q_len %lld", r, kv_len, q_len); return POD_ERR_INVALID_ARG; }
+        if (q_start < 0) { err = fmt("request %lld: negative q_start", r); return POD_ERR_INVALID_ARG; }
+        if (row < 0 || row >= prm.n_cache_rows) { err = fmt("request %lld: cache_row %lld out of range", r, row); return POD_ERR_INVALID_ARG; }
+        if (paged) {
+            if (ceil_div(kv_len, prm.block_size) > prm.max_blocks_per_seq) {
+                err = fmt("request %lld: kv_len %lld needs more than max_blocks_per_seq blocks", r, kv_len);
+                return POD_ERR_INVALID_ARG;
+            }
+        } else if ((int64_t)kv_len * token_elems > prm.kv_seq_stride) {
+            err = fmt("request %lld: kv_len %lld does not fit in kv_seq_stride", r, kv_len);
+            return POD_ERR_INVALID_ARG;
+        }
+        if (r < prm.n_prefill) {
+            spans.emplace_back(q_start, q_len);
+            n_prefill_rows = std::max<int64_t>(n_prefill_rows, (int64_t)q_start + q_len);
+        } else {
+            if (q_len != 1) { err = fmt("decode request %lld: q_len must be 1", r); return POD_ERR_INVALID_ARG; }
+            if (q_start >= prm.n_decode) { err = fmt("decode request %lld: q_start out of range", r); return POD_ERR_INVALID_ARG; }
+            if (decode_row_used[(size_t)q_start]) { err = fmt("decode request %lld: q_start used twice", r); return POD_ERR_INVALID_ARG; }
+            decode_row_used[(size_t)q_start] = 1;
+        }
+    }
+    std::sort(spans.begin(), spans.end());
+    for (size_t i = 1; i < spans.size(); ++i)
+        if (spans[i - 1].first + spans[i - 1].second > spans[i].first) {
+            err = "prefill query ranges overlap";
+            return POD_ERR_INVALID_ARG;
+        }
+    if (n_prefill_rows > (int64_t)1 << 30) { err = "too many prefill rows"; return POD_ERR_INVALID_ARG; }
+
+    plan = Plan();
+    plan.prm = prm;
+    plan.n_cus = n_cus;
+    plan.group = group;
+    plan.meta.assign(seq_meta, seq_meta + 4 * (size_t)n_req);
+    plan.n_prefill_rows = n_prefill_rows;
+
+    int64_t next_prow = 0;
+
+    // ---- prefill items -----------------------------------------------------------------
+    // Row blocks of 128 packed rows per K/V head; split-KV only when there are too few blocks to
+    // fill the chip, and never beyond `max_prefill_waves` chip-wide rounds (Section 4.2.4).
+    {
+        int64_t base_items = 0;
+        for (int r = 0; r < prm.n_prefill; ++r)
+            base_items += (int64_t)prm.n_kv_heads * ceil_div(seq_meta[4 * r + 1] * group, kPrefillRows);
+        const int waves = prm.max_prefill_waves > 0 ? prm.max_prefill_waves : 2;
+        const int64_t cap_items = (int64_t)waves * n_cus;
+        const int s_cap = base_items > 0 ? (int)std::max<int64_t>(1, cap_items / base_items) : 1;
+        const int min_split = round_up(prm.prefill_split_len > 0 ? prm.prefill_split_len : 1024, kPrefillKvTile);
+        for (int r = 0; r < prm.n_prefill; ++r) {
+            const int q_len = seq_meta[4 * r + 1], kv_len = seq_meta[4 * r + 2];
+            const int prefix = kv_len - q_len;
+            const int rows_total = q_len * group;
+            for (int kvh = 0; kvh < prm.n_kv_heads; ++kvh)
+                for (int row0 = 0; row0 < rows_total; row0 += kPrefillRows) {
+                    const int n_rows = std::min(kPrefillRows, rows_total - row0);
+                    const int last_tok = (row0 + n_rows - 1) / group;
+                    const int kmax = prefix + last_tok + 1;          // keys this block can see
+                    const int n_tiles = ceil_div(kmax, kPrefillKvTile);
+                    int s = std::min(s_cap, std::max(1, kmax / min_split));
+                    const int tps = ceil_div(n_tiles, s);
+                    s = ceil_div(n_tiles, tps);
+                    int64_t prow_base = -1;
+                    if (s > 1) {
+                        prow_base = next_prow;
+                        next_prow += (int64_t)s * kPrefillRows;
+                        plan.centries.push_back(CombineEntry{kPrefill, r, kvh, row0, n_rows, s,
+                                                             (int32_t)prow_base, kPrefillRows});
+                    }
+                    for (int i = 0; i < s; ++i) {
+                        PrefillItem it;
+                        it.req = r; it.kv_head = kvh; it.row0 = row0; it.n_rows = n_rows;
+                        it.kv_begin = i * tps * kPrefillKvTile;
+                        it.kv_end = std::min(kmax, (i + 1) * tps * kPrefillKvTile);
+                        it.prow0 = s > 1 ? (int32_t)(prow_base + (int64_t)i * kPrefillRows) : -1;
+                        it.split = i;
+                        plan.pitems.push_back(it);
+                    }
+                    plan.max_psplits = std::max(plan.max_psplits, s);
+                }
+        }
+        // Longest first: work ids are claimed in order, so the long items start early.
+        std::stable_sort(plan.pitems.begin(), plan.pitems.end(), [](const PrefillItem &x, const PrefillItem &y) {
+            return (x.kv_end - x.kv_begin) > (y.kv_end - y.kv_begin);
+        });
+    }
+
+    // ---- decode units ------------------------------------------------------------------
+    {
+        int64_t token_heads = 0;
+        for (int r = prm.n_prefill; r < n_req; ++r) token_heads += (int64_t)seq_meta[4 * r + 2] * prm.n_kv_heads;
+        int chunk = prm.decode_chunk;
+        if (chunk <= 0) {
+            // Aim at about four units per resident wavefront slot so ragged contexts balance,
+            // but keep units long enough that their prologue and partial rows stay negligible.
+            const int64_t slots = (int64_t)n_cus * 8;
+            chunk = (int)std::min<int64_t>(2048, std::max<int64_t>(256, (token_heads + 4 * slots - 1) / (4 * slots)));
+        }
+        chunk = round_up(std::max(chunk, kDecodeStep), kDecodeStep);
+        plan.decode_chunk = chunk;
+        for (int r = prm.n_prefill; r < n_req; ++r) {
+            const int kv_len = seq_meta[4 * r + 2];
+            const int s = ceil_div(kv_len, chunk);
+            const int tps = round_up(ceil_div(kv_len, s), kDecodeStep);
+            const int s_eff = ceil_div(kv_len, tps);
+            for (int kvh = 0; kvh < prm.n_kv_heads; ++kvh) {
+                int64_t prow_base = -1;
+                if (s_eff > 1) {
+                    prow_base = next_prow;
+                    next_prow += (int64_t)s_eff * group;
+                    plan.centries.push_back(CombineEntry{kDecode, r, kvh, 0, group, s_eff, (int32_t)prow_base, group});
+                }
+                for (int i = 0; i < s_eff; ++i) {
+                    DecodeUnit u;
+                    u.req = r; u.kv_head = kvh;
+                    u.t0 = i * tps;
+                    u.t1 = std::min(kv_len, (i + 1) * tps);
+                    u.prow0 = s_eff > 1 ? (int32_t)(prow_base + (int64_t)i * group) : -1;
+                    u.split = i; u.pad0 = 0; u.pad1 = 0;
+                    plan.dunits.push_back(u);
+                }
+                plan.max_dsplits = std::max(plan.max_dsplits, s_eff);
+            }
+        }
+        std::stable_sort(plan.dunits.begin(), plan.dunits.end(), [](const DecodeUnit &x, const DecodeUnit &y) {
+            return (x.t1 - x.t0) > (y.t1 - y.t0);
+        });
+        plan.n_dwgs = ceil_div((int)plan.dunits.size(), kWavesPerWg);
+    }
+    if (next_prow > (int64_t)1 << 30) { err = "too many partial rows"; return POD_ERR_INVALID_ARG; }
+    plan.n_partial_rows = next_prow;
+
+    role_ratio(prm.policy, (int)plan.pitems.size(), plan.n_dwgs, plan.p_ratio, plan.d_ratio);
+
+    // ---- workspace layout --------------------------------------------------------------
+    size_t off = align256(sizeof(WsHeader));
+    plan.off_pitems = off;   off = align256(off + plan.pitems.size() * sizeof(PrefillItem));
+    plan.off_dunits = off;   off = align256(off + plan.dunits.size() * sizeof(DecodeUnit));
+    plan.off_centries = off; off = align256(off + plan.centries.size() * sizeof(CombineEntry));
+    plan.off_part_o = off;   off = align256(off + (size_t)plan.n_partial_rows * prm.head_dim * sizeof(float));
+    plan.off_part_ml = off;  off = align256(off + (size_t)plan.n_partial_rows * 2 * sizeof(float));
+    plan.ws_bytes = off;
+    return POD_OK;
+}
+
+}  // namespace pod

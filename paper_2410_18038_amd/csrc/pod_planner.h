@@ -1,0 +1,44 @@
+// Host-side plan: how one hybrid batch is cut into prefill items, decode units and combine
+// groups, and where each table lives in the device workspace.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/pod_attn.h"
+#include "pod_common.h"
+
+namespace pod {
+
+struct Plan {
+    pod_attn_params prm;
+    int n_cus = 256;
+    int group = 1;
+    std::vector<int32_t> meta;              // host copy of seq_meta
+    std::vector<PrefillItem> pitems;
+    std::vector<DecodeUnit> dunits;
+    std::vector<CombineEntry> centries;
+    int64_t n_prefill_rows = 0;
+    int64_t n_partial_rows = 0;
+    int p_ratio = 1, d_ratio = 1;
+    int decode_chunk = 0;
+    int max_psplits = 1, max_dsplits = 1;
+    int n_dwgs = 0;
+    // byte offsets inside the workspace (each 256-byte aligned)
+    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_part_o = 0, off_part_ml = 0;
+    size_t ws_bytes = 0;
+    // side streams and events of the two-stream mode, created on first use
+    void *side_stream[2] = {nullptr, nullptr};
+    void *events[3] = {nullptr, nullptr, nullptr};
+};
+
+// Validates and fills `plan`; returns POD_OK or an error code with a message in `err`.
+pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n_cus, Plan &plan,
+                      std::string &err);
+
+// Reduce a (prefill workgroups : decode workgroups) count to the small role ratio of Section 4.1.
+void role_ratio(int policy, int n_prefill_wgs, int n_decode_wgs, int &p, int &d);
+
+}  // namespace pod

@@ -1,0 +1,346 @@
+"""CPU tests of the C-ABI library: symbols, argument validation, the host planner, the binder model.
+
+No compute call is made here; the planner needs no GPU once n_compute_units is given.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2410_18038_amd import pod
+from paper_2410_18038_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def params_for(batch, **kw):
+    base = dict(n_prefill=batch.n_prefill, n_decode=batch.n_decode, n_q_heads=batch.n_q_heads,
+                n_kv_heads=batch.n_kv_heads, head_dim=batch.head_dim, dtype=batch.dtype,
+                softmax_scale=batch.softmax_scale, block_size=batch.block_size,
+                max_blocks_per_seq=batch.max_blocks_per_seq, n_cache_rows=batch.n_cache_rows,
+                n_blocks=batch.n_blocks, kv_seq_stride=batch.kv_seq_stride, n_compute_units=256)
+    base.update(kw)
+    return pod.make_params(**base)
+
+
+def meta_only(name, prefill, decodes, hq=32, hkv=8, d=128, block_size=16):
+    """A batch descriptor without tensors worth mentioning (tiny head_dim is not allowed, so keep d)."""
+    n_seqs = len(prefill) + len(decodes)
+    meta = np.zeros((n_seqs, 4), dtype=np.int32)
+    q0 = 0
+    for r, (q_len, kv_len) in enumerate(prefill):
+        meta[r] = (q0, q_len, kv_len, r)
+        q0 += q_len
+    for i, kv_len in enumerate(decodes):
+        meta[len(prefill) + i] = (i, 1, kv_len, len(prefill) + i)
+    longest = int(meta[:, 2].max()) if n_seqs else 1
+    prm = pod.make_params(n_prefill=len(prefill), n_decode=len(decodes), n_q_heads=hq, n_kv_heads=hkv,
+                          head_dim=d, dtype=wl.BF16, softmax_scale=d ** -0.5, block_size=block_size,
+                          max_blocks_per_seq=(longest + 15) // 16 if block_size else 0, n_cache_rows=max(n_seqs, 1),
+                          n_blocks=10 ** 6 if block_size else 0,
+                          kv_seq_stride=0 if block_size else longest * hkv * d, n_compute_units=256)
+    return prm, meta
+
+
+# -- the library and its symbols ------------------------------------------------------------- #
+def test_library_loads_and_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pod_attn.h")).read()
+    declared = sorted(set(re.findall(r"\b(pod_attn_[a-z_]+)\s*\(", header)))
+    assert declared, "no declarations found in the header"
+    lib = ctypes.CDLL(pod.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in include/pod_attn.h but not exported"
+    assert sorted(pod.EXPORTS) == declared
+    assert "gfx950" in pod.pod_attn_version()
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """Compile the public header as plain C and compare struct sizes and a few offsets with ctypes."""
+    import subprocess
+    src = tmp_path / "sizes.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <stddef.h>\n#include "pod_attn.h"\n'
+        'int main(void){printf("%zu %zu %zu %zu %zu\\n", sizeof(pod_attn_params), sizeof(pod_attn_plan_info),'
+        ' offsetof(pod_attn_params, kv_seq_stride), offsetof(pod_attn_params, n_compute_units),'
+        ' offsetof(pod_attn_plan_info, workspace_bytes)); return 0;}\n')
+    exe = tmp_path / "sizes"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert got == [ctypes.sizeof(pod.Params), ctypes.sizeof(pod.PlanInfo), pod.Params.kv_seq_stride.offset,
+                   pod.Params.n_compute_units.offset, pod.PlanInfo.workspace_bytes.offset]
+
+
+# -- validation ------------------------------------------------------------------------------- #
+def test_invalid_arguments_are_rejected_with_a_message():
+    b = wl.config_batch(1)
+    good = params_for(b)
+    pod.pod_attn_plan_create(good, b.seq_meta).close()
+
+    def expect(status, prm=None, meta=None):
+        with pytest.raises(pod.PodError) as e:
+            pod.pod_attn_plan_create(prm or params_for(b), b.seq_meta if meta is None else meta)
+        assert e.value.status == status, str(e.value)
+        assert len(str(e.value)) > 20
+
+    expect(-1, params_for(b, n_kv_heads=3))
+    expect(-2, params_for(b, head_dim=96))
+    expect(-2, params_for(b, dtype=5))
+    expect(-2, params_for(b, n_q_heads=32, n_kv_heads=1))          # 32 query heads on one K/V head
+    expect(-1, params_for(b, softmax_scale=0.0))
+    expect(-1, params_for(b, softmax_scale=float("nan")))
+    expect(-1, params_for(b, kv_seq_stride=0))
+    expect(-1, params_for(b, block_size=16, max_blocks_per_seq=0))
+    for col, val in [(1, 0), (2, 100), (3, 99), (0, -1)]:          # q_len 0; kv_len < q_len; row; q_start
+        m = b.seq_meta.copy()
+        m[0, col] = val
+        expect(-1, meta=m)
+    m = b.seq_meta.copy()
+    m[b.n_prefill, 1] = 2                                             # a decode with two query tokens
+    expect(-1, meta=m)
+    m = b.seq_meta.copy()
+    m[b.n_prefill + 1, 0] = m[b.n_prefill, 0]                        # two decodes on one output row
+    expect(-1, meta=m)
+    m = b.seq_meta.copy()
+    m[0, 2] = 513                                                     # longer than the cache slot
+    expect(-1, meta=m)
+
+
+def test_forward_rejects_missing_buffers_without_touching_the_gpu():
+    b = wl.config_batch(1)
+    plan = pod.pod_attn_plan_create(params_for(b), b.seq_meta)
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_attn_forward(0, 0, 0, 0, 0, 0, 0, plan, 0, 0)
+    assert e.value.status == -1
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_attn_forward(8, 8, 8, 8, 8, 0, 8, plan, 0, 0)
+    assert e.value.status == -3
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_attn_forward(8, 8, 8, 8, 8, 0, 8, plan, 256, 1 << 30, mode=9)
+    assert e.value.status == -1
+    plan.close()
+
+
+# -- planner: every (row, key) pair and every decode token is covered exactly once --------------- #
+def coverage_check(prm, meta):
+    plan = pod.pod_attn_plan_create(prm, meta)
+    info = plan.info()
+    group = prm.n_q_heads // prm.n_kv_heads
+    items, units = plan.prefill_items(), plan.decode_units()
+    assert len(items) == info.n_prefill_items and len(units) == info.n_decode_units
+    assert info.fused_grid == len(items) + (len(units) + 3) // 4
+    # prefill: per (request, kv head, row block) the key ranges tile [0, kmax) without gaps
+    blocks = {}
+    for req, kvh, row0, n_rows, k0, k1, prow0, split in items:
+        assert row0 % 128 == 0 and 1 <= n_rows <= 128 and k0 % 64 == 0 and k0 < k1
+        blocks.setdefault((req, kvh, row0, n_rows), []).append((k0, k1, prow0, split))
+    want_blocks = 0
+    for r in range(prm.n_prefill):
+        q_len, kv_len = int(meta[r, 1]), int(meta[r, 2])
+        rows = q_len * group
+        for kvh in range(prm.n_kv_heads):
+            for row0 in range(0, rows, 128):
+                n_rows = min(128, rows - row0)
+                kmax = kv_len - q_len + (row0 + n_rows - 1) // group + 1
+                parts = sorted(blocks[(r, kvh, row0, n_rows)])
+                assert parts[0][0] == 0 and parts[-1][1] == kmax
+                for a, b in zip(parts, parts[1:]):
+                    assert a[1] == b[0]
+                assert all((p[2] >= 0) == (len(parts) > 1) for p in parts)
+                assert sorted(p[3] for p in parts) == list(range(len(parts)))
+                want_blocks += 1
+    assert len(blocks) == want_blocks
+    # decode: token ranges tile [0, kv_len)
+    ranges = {}
+    for req, kvh, t0, t1, prow0, split, _, _ in units:
+        assert t0 % 32 == 0 and t0 < t1
+        ranges.setdefault((req, kvh), []).append((t0, t1, prow0))
+    for r in range(prm.n_prefill, prm.n_prefill + prm.n_decode):
+        for kvh in range(prm.n_kv_heads):
+            parts = sorted(ranges[(r, kvh)])
+            assert parts[0][0] == 0 and parts[-1][1] == int(meta[r, 2])
+            for a, b in zip(parts, parts[1:]):
+                assert a[1] == b[0]
+            assert all((p[2] >= 0) == (len(parts) > 1) for p in parts)
+    assert len(ranges) == prm.n_decode * prm.n_kv_heads
+    # partial rows do not overlap
+    spans = [(p, p + 128) for *_, p, _ in [tuple(i) for i in items] if p >= 0]
+    spans += [(int(u[4]), int(u[4]) + group) for u in units if u[4] >= 0]
+    spans.sort()
+    for a, b in zip(spans, spans[1:]):
+        assert a[1] <= b[0]
+    assert (spans[-1][1] if spans else 0) <= info.n_partial_rows
+    # longest-first ordering
+    lens = [i[5] - i[4] for i in items]
+    assert lens == sorted(lens, reverse=True)
+    lens = [u[3] - u[2] for u in units]
+    assert lens == sorted(lens, reverse=True)
+    assert pod.pod_attn_workspace_size(plan) == info.workspace_bytes >= 4352
+    plan.close()
+    return info
+
+
+@pytest.mark.parametrize("config,index", [(1, 0), (5, 0), (5, 11)])
+def test_plan_covers_small_benchmark_batches(config, index):
+    b = wl.config_batch(config, index) if config == 1 else None
+    if b is not None:
+        coverage_check(params_for(b), b.seq_meta)
+        return
+    chunk, nd = wl.RATIO_SWEEP[index]
+    rng = np.random.Generator(np.random.PCG64(index))
+    prm, meta = meta_only("sweep", [(chunk, 4096)], rng.integers(4096, 16385, size=nd).tolist())
+    coverage_check(prm, meta)
+
+
+def test_plan_shapes_for_the_large_configs():
+    # config 2: 32 heads x 8 row blocks = 256 items, no split (256 items already fill 256 units once,
+    # and two rounds allow 512 -> 2 splits of >= 1024 keys)
+    prm, meta = meta_only("c2", [(1024, 4096)], [4096] * 64, hq=32, hkv=32, block_size=0)
+    info = coverage_check(prm, meta)
+    assert info.n_prefill_items in (256, 512) and info.max_prefill_splits <= 2
+    assert info.n_decode_units == 64 * 32 * info.max_decode_splits
+    # config 4: 4 kv heads x 128 row blocks = 512 items = two rounds -> no split (Section 4.2.4)
+    prm, meta = meta_only("c4", [(2048, 32768)], [32768] * 32, hq=32, hkv=4)
+    info = coverage_check(prm, meta)
+    assert info.n_prefill_items == 512 and info.max_prefill_splits == 1
+    # config 3: 128 row blocks -> splits allowed up to 4 (512 items)
+    prm, meta = meta_only("c3", [(512, 8192)], [9000] * 128, hq=32, hkv=8)
+    info = coverage_check(prm, meta)
+    assert info.max_prefill_splits == 4 and info.n_prefill_items <= 512
+
+
+def test_split_cap_follows_max_prefill_waves():
+    """Section 4.2.4: prefill work items fill at most `max_prefill_waves` chip-wide rounds."""
+    prm, meta = meta_only("cap", [(256, 8192)], [4096] * 8)
+    for waves, limit in [(1, 256), (2, 512), (4, 1024)]:
+        prm.max_prefill_waves = waves
+        prm.prefill_split_len = 64
+        info = coverage_check(prm, meta)
+        assert info.n_prefill_items <= limit
+        assert info.n_prefill_items > limit // 2
+
+
+def test_ragged_and_degenerate_batches_plan_cleanly():
+    for prefill, decodes in [([], [1]), ([(1, 1)], []), ([(129, 129), (7, 4000)], [1, 31, 33, 5000]),
+                             ([(2048, 2048)], [])]:
+        prm, meta = meta_only("rag", prefill, decodes, hq=8, hkv=2)
+        coverage_check(prm, meta)
+    prm, meta = meta_only("empty", [], [])
+    plan = pod.pod_attn_plan_create(prm, np.zeros((0, 4), dtype=np.int32))
+    assert plan.info().fused_grid == 0
+    plan.close()
+
+
+# -- role ratio and the binder model -------------------------------------------------------------- #
+def read_golden(name):
+    rows = []
+    for line in open(os.path.join(GOLDEN, name)):
+        line = line.split("#")[0].strip()
+        if line:
+            rows.append(line.split())
+    return rows
+
+
+def test_proportional_policy_reproduces_the_papers_example():
+    """Section 5.4.2: 50 prefill and 100 decode CTAs give the per-unit order prefill, decode, decode."""
+    (n_p, n_d, pattern), = read_golden("policy_example.txt")
+    n_p, n_d = int(n_p), int(n_d)
+    prm, meta = meta_only("pol", [(128 * n_p // 2, 128 * n_p // 2)], [256] * (n_d * 4 // 2), hq=2, hkv=2,
+                          block_size=0)
+    prm.decode_chunk = 256
+    prm.prefill_split_len = 1 << 20          # one item per row block
+    plan = pod.pod_attn_plan_create(prm, meta)
+    info = plan.info()
+    assert (info.n_prefill_items, (info.n_decode_units + 3) // 4) == (n_p, n_d)
+    assert (info.prefill_ratio, info.decode_ratio) == (1, 2)
+    plan.close()
+    # all arrivals on one compute unit, nobody leaves: roles must follow the printed pattern
+    served, roles, items = pod.pod_attn_simulate_binder(n_p, n_d, 1, 2, np.zeros(12, dtype=np.int32))
+    assert "".join("PD"[r] for r in roles) == pattern * 4
+    # 50:50 alternates
+    prm.policy = pod.POLICY_ALTERNATE
+    plan = pod.pod_attn_plan_create(prm, meta)
+    assert (plan.info().prefill_ratio, plan.info().decode_ratio) == (1, 1)
+    plan.close()
+    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.zeros(6, dtype=np.int32))
+    assert "".join("PD"[r] for r in roles) == "PDPDPD"
+
+
+def test_wave_quantization_example():
+    """Section 3.2: 54 decodes x 4 K/V heads = 216 CTAs = two full rounds of 108 units; 55 -> 220."""
+    for n_dec, heads, units, ctas, rounds in [tuple(int(x) for x in r) for r in read_golden("wave_quantization.txt")]:
+        assert n_dec * heads == ctas
+        assert -(-ctas // units) == rounds
+        prm, meta = meta_only("wq", [], [16384] * n_dec, hq=32, hkv=heads)
+        prm.decode_chunk = 16384
+        plan = pod.pod_attn_plan_create(prm, meta)
+        assert plan.info().n_decode_units == ctas          # one unit per (request, K/V head)
+        plan.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_binder_hands_out_every_work_id_exactly_once(seed):
+    """Whatever unit each workgroup lands on and whenever others leave, prefill ids 0..P-1 and decode
+    ids 0..D-1 are each claimed once and nobody is left without work (Section 4.1: the scheme does
+    not depend on how the hardware places workgroups)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_p, n_d = int(rng.integers(0, 300)), int(rng.integers(0, 900))
+    if n_p + n_d == 0:
+        n_d = 5
+    p_ratio, d_ratio = int(rng.integers(1, 5)), int(rng.integers(1, 9))
+    if n_p == 0:
+        p_ratio = 0
+    if n_d == 0:
+        d_ratio = 0
+    n_units = int(rng.choice([1, 7, 256]))
+    events, alive, arrivals = [], [], 0
+    while arrivals < n_p + n_d:
+        if alive and rng.random() < 0.45:
+            who = alive.pop(int(rng.integers(len(alive))))
+            events.append(-who - 1)
+        else:
+            events.append(int(rng.integers(n_units)) * 3 % 1024)
+            alive.append(arrivals)
+            arrivals += 1
+    served, roles, items = pod.pod_attn_simulate_binder(n_p, n_d, p_ratio, d_ratio, np.array(events, dtype=np.int32))
+    assert served == n_p + n_d and (roles >= 0).all()
+    assert sorted(items[roles == 0].tolist()) == list(range(n_p))
+    assert sorted(items[roles == 1].tolist()) == list(range(n_d))
+    # one arrival too many gets nothing
+    served2, roles2, items2 = pod.pod_attn_simulate_binder(n_p, n_d, p_ratio, d_ratio,
+                                                           np.array(events + [0], dtype=np.int32))
+    assert served2 == served and roles2[-1] == -1 and items2[-1] == -1
+
+
+def test_binder_keeps_both_operations_resident_on_each_unit():
+    """Two slots per unit, long prefill items, short decode workgroups: every unit keeps one of each
+    while both kinds of work remain, which the plain ticket rule alone would not do."""
+    n_units, n_p, n_d = 4, 8, 200
+    events, resident = [], {u: [] for u in range(n_units)}    # unit -> list of (arrival, role unknown yet)
+    roles_so_far = []
+    arrivals = 0
+    # fill both slots of every unit
+    for u in range(n_units):
+        for _ in range(2):
+            events.append(u)
+            resident[u].append(arrivals)
+            arrivals += 1
+    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
+    for u in range(n_units):
+        assert sorted(roles[resident[u]].tolist()) == [0, 1]
+    # decode workgroups finish and are replaced 20 times per unit; prefill ones stay
+    for _ in range(20):
+        for u in range(n_units):
+            _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
+            leaving = [a for a in resident[u] if roles[a] == 1][0]
+            events.append(-leaving - 1)
+            resident[u].remove(leaving)
+            events.append(u)
+            resident[u].append(arrivals)
+            arrivals += 1
+    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
+    for u in range(n_units):
+        assert sorted(roles[resident[u]].tolist()) == [0, 1]

@@ -1,0 +1,131 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle, element by element.
+
+Bar (max-abs over the whole batch, GPU 16-bit output widened to fp64): 2e-3 for fp16 inputs,
+1e-2 for bf16 inputs; fp32 accumulation on the GPU.  Every call goes through the C ABI.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2410_18038_amd import pod
+from paper_2410_18038_amd import workloads as wl
+from tests.helpers import oracle_out
+
+pytestmark = pytest.mark.gpu
+
+TOL = {wl.F16: 2e-3, wl.BF16: 1e-2}
+ALL_MODES = ["fused", "serial", "streams"]
+
+
+def run_gpu(batch, mode="fused", **plan_kw):
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch, **plan_kw)
+    out = attn.forward(dev_batch, mode=pod.MODES[mode])
+    torch.cuda.synchronize()
+    res = out.to(torch.float64).cpu().numpy()
+    info = attn.info
+    attn.close()
+    return res, info
+
+
+def check(batch, mode="fused", rows=None, **plan_kw):
+    print(f"case {batch.name} mode={mode} {plan_kw}", flush=True)
+    got, info = run_gpu(batch, mode, **plan_kw)
+    want = oracle_out(batch, rows=rows)
+    if rows is not None:
+        got = got[rows]
+    assert np.isfinite(got).all(), "non-finite GPU output"
+    err = np.abs(got - want).max()
+    assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} > {TOL[batch.dtype]:.0e} ({batch.name}, {mode})"
+    return err, info
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+def test_config1_tiny_hybrid_batch(mode):
+    check(wl.config_batch(1, poison=float("nan")), mode)
+
+
+@pytest.mark.parametrize("mode", ["prefill_only", "decode_only"])
+def test_single_operation_modes_write_only_their_rows(mode):
+    batch = wl.config_batch(1, poison=float("nan"))
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch)
+    out = torch.full((batch.n_rows, batch.n_q_heads, batch.head_dim), 7.0, dtype=batch.torch_dtype, device="cuda:0")
+    attn.forward(dev_batch, out=out, mode=pod.MODES[mode])
+    torch.cuda.synchronize()
+    got = out.to(torch.float64).cpu().numpy()
+    want = oracle_out(batch)
+    npr = batch.n_prefill_rows
+    mine = slice(0, npr) if mode == "prefill_only" else slice(npr, None)
+    other = slice(npr, None) if mode == "prefill_only" else slice(0, npr)
+    assert np.abs(got[mine] - want[mine]).max() <= TOL[batch.dtype]
+    assert (got[other] == 7.0).all()
+    attn.close()
+
+
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (8, 1), (16, 1)])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_shapes_dtypes_layouts(dtype, hq, hkv, d, block_size):
+    """Several tiles and ragged tails in both operations; cache tails and spare blocks poisoned."""
+    batch = wl.make_batch(f"grid-{hq}/{hkv}-d{d}-bs{block_size}", prefill=[(200, 333), (37, 37)],
+                          decode_kv_lens=[1, 31, 32, 33, 257, 700], n_q_heads=hq, n_kv_heads=hkv,
+                          head_dim=d, dtype=dtype, seed=1000 + hq * 7 + hkv + d + block_size,
+                          block_size=block_size, poison=float("nan"))
+    check(batch, "fused")
+
+
+@pytest.mark.parametrize("mode", ALL_MODES)
+@pytest.mark.parametrize("block_size", [0, 16, 48])
+def test_split_kv_paths(mode, block_size):
+    """Force split-KV in both operations (short chunks, tiny split lengths) and merge the partials."""
+    batch = wl.make_batch(f"split-bs{block_size}", prefill=[(96, 1500)], decode_kv_lens=[1200, 90, 2047, 640],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.BF16, seed=77 + block_size,
+                          block_size=block_size, poison=float("nan"))
+    err, info = check(batch, mode, decode_chunk=256, prefill_split_len=256, max_prefill_waves=64)
+    assert info.max_prefill_splits > 1 and info.max_decode_splits > 1
+
+
+def test_degenerate_batches():
+    """Only prefill, only decode, one key, a chunk without prefix."""
+    for name, prefill, decodes in [("only-prefill", [(65, 65)], []), ("only-decode", [], [1, 5, 64]),
+                                   ("one-key", [(1, 1)], [1]), ("no-prefix", [(130, 130)], [3])]:
+        batch = wl.make_batch(name, prefill=prefill, decode_kv_lens=decodes, n_q_heads=4, n_kv_heads=2,
+                              head_dim=64, dtype=wl.F16, seed=5, poison=float("nan"))
+        for mode in ALL_MODES:
+            check(batch, mode)
+
+
+def test_repeated_launches_are_bit_identical_and_counters_reset():
+    """The binder changes who computes a work item, never what it computes."""
+    batch = wl.make_batch("repeat", prefill=[(300, 900)], decode_kv_lens=[500] * 40 + [33, 1000],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.F16, seed=9, block_size=16)
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch, decode_chunk=128)
+    first = attn.forward(dev_batch).clone()
+    for _ in range(20):
+        again = attn.forward(dev_batch)
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))
+    serial = attn.forward(dev_batch, mode=pod.MODE_SERIAL)
+    assert torch.equal(first.view(torch.int16), serial.view(torch.int16))
+    torch.cuda.synchronize()
+    hdr = attn.workspace[(attn.ws_ptr - attn.workspace.data_ptr()):][:4352].view(torch.int32)
+    assert int(hdr.abs().sum()) == 0, "binder counters not back at zero after the launches"
+    attn.close()
+
+
+def test_decode_through_prefill_path_matches_decode_path():
+    """A decode submitted as a one-token prefill chunk must agree with the decode path."""
+    lens = [77, 512, 1025]
+    as_decode = wl.make_batch("dec", prefill=[], decode_kv_lens=lens, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                              dtype=wl.F16, seed=13)
+    as_prefill = wl.make_batch("pre", prefill=[(1, l) for l in lens], decode_kv_lens=[], n_q_heads=8,
+                               n_kv_heads=2, head_dim=128, dtype=wl.F16, seed=14, max_len=as_decode.max_len)
+    as_prefill.prefill_q.copy_(as_decode.decode_q)
+    as_prefill.k_cache.copy_(as_decode.k_cache)
+    as_prefill.v_cache.copy_(as_decode.v_cache)
+    a, _ = run_gpu(as_decode)
+    b, _ = run_gpu(as_prefill)
+    assert np.abs(a - b).max() <= 2e-3
+    assert np.abs(a - oracle_out(as_decode)).max() <= 2e-3
