@@ -60,6 +60,11 @@ typedef enum {
     POD_MODE_DECODE_ONLY = 4    /* only the decode rows of `out` are written                       */
 } pod_mode;
 
+/* May be OR-ed into `mode`: leave the split-KV partials in the workspace and skip the combine
+ * pass, so that a profiler or a pair of events sees the attention kernel alone.  Rows whose
+ * work was split are then not written to `out`. */
+#define POD_MODE_FLAG_NO_COMBINE 0x100
+
 /* Which operation a workgroup takes first on its compute unit (Section 4.1, the two policies). */
 typedef enum {
     POD_POLICY_AUTO = 0,
@@ -159,7 +164,8 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  *   workspace   as prepared by pod_attn_plan_upload with this plan.
  *
  * The device arrays are trusted: a seq_meta that differs from the planned one, or a block
- * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode.
+ * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode, optionally OR-ed with
+ * POD_MODE_FLAG_NO_COMBINE.
  */
 pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
                             const void *k_cache, const void *v_cache,

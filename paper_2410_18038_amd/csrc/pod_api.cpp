@@ -200,6 +200,8 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     pod::Plan &p = const_cast<pod_attn_plan *>(plan)->p;
     const bool paged = p.prm.block_size > 0;
     const int n_req = p.prm.n_prefill + p.prm.n_decode;
+    const bool no_combine = (mode & POD_MODE_FLAG_NO_COMBINE) != 0;
+    mode &= ~POD_MODE_FLAG_NO_COMBINE;
     if (mode < POD_MODE_FUSED || mode > POD_MODE_DECODE_ONLY) return fail(POD_ERR_INVALID_ARG, "unknown mode");
     if (n_req == 0) return POD_OK;
     if (!k_cache || !v_cache || !seq_meta || !out) return fail(POD_ERR_INVALID_ARG, "k_cache, v_cache, seq_meta or out is null");
@@ -214,6 +216,7 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     const int dt = p.prm.dtype, hd = p.prm.head_dim;
     hipError_t e = hipSuccess;
     auto go = [&](int which, const pod::KernelArgs &args, hipStream_t on) {
+        if (which == pod::kLaunchCombine && no_combine) return;
         if (e == hipSuccess) e = pod::launch(which, args, dt, hd, paged, on);
     };
 

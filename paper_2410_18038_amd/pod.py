@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libpod_attn.so")
 POD_OK = 0
 F16, BF16 = 0, 1
 MODE_FUSED, MODE_SERIAL, MODE_STREAMS, MODE_PREFILL_ONLY, MODE_DECODE_ONLY = range(5)
+MODE_FLAG_NO_COMBINE = 0x100
 MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
          "prefill_only": MODE_PREFILL_ONLY, "decode_only": MODE_DECODE_ONLY}
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
@@ -67,6 +68,12 @@ def lib():
             raise ImportError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2410_18038_amd.build` "
                 "(hipcc, gfx950). This package has no fallback path.")
+        # The library must share torch's HIP runtime (streams, events and device memory are torch's):
+        # torch bundles its own libamdhip64 under the same soname, so it has to be loaded first.
+        import torch
+        bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+        if os.path.exists(bundled):
+            ctypes.CDLL(bundled, mode=ctypes.RTLD_GLOBAL)
         L = ctypes.CDLL(LIB_PATH)
         vp, i32p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int32)
         L.pod_attn_plan_create.restype = ctypes.c_int
