@@ -132,6 +132,17 @@ pod_status pod_attn_plan_create(const pod_attn_params *params, const int32_t *se
 void       pod_attn_plan_destroy(pod_attn_plan *plan);
 pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info *info);
 
+/*
+ * Optional execution trace, the evidence for co-location (Section 4.1 wants both operations
+ * resident on every multiprocessor).  `trace` is device memory of at least 32 bytes per workgroup
+ * of the fused launch (pod_attn_plan_info.fused_grid), or NULL to switch tracing off.  After a
+ * forward call record w holds, as int32 {unit id, role (0 prefill / 1 decode), work id, kernel}
+ * followed by two uint64 device timestamps (100 MHz) of the workgroup's begin and end.  The
+ * fused kernel indexes records by workgroup; the stand-alone kernels by prefill item, then by
+ * decode workgroup.  Tracing adds two clock reads and one 32-byte store per workgroup.
+ */
+pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes);
+
 /* Bytes of device workspace the plan needs (work tables, counters, split partials). */
 size_t     pod_attn_workspace_size(const pod_attn_plan *plan);
 
@@ -201,6 +212,18 @@ int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items
  */
 pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
 pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
+
+/*
+ * Measurement aids (Section 5.1 reports compute and bandwidth utilisation; these give the two
+ * ceilings this GPU actually sustains).  Both enqueue one kernel on `stream`; the caller times it.
+ *   pod_attn_probe_hbm_read: reads `bytes` of device memory at `buf` once, fully coalesced.
+ *   pod_attn_probe_mfma:     every wavefront of a chip-filling grid issues 4*iters dense fp16 MFMA
+ *                            (32x32x16) instructions; *flops_out (host, may be NULL) receives the
+ *                            total flop count.
+ * `sink` is 16 bytes of device memory that is never written in practice.
+ */
+pod_status pod_attn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream);
+pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, void *stream);
 
 const char *pod_attn_last_error(void);
 const char *pod_attn_version(void);

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpod_attn.so")
-SOURCES = ["pod_kernels.hip", "pod_planner.cpp", "pod_api.cpp"]
+SOURCES = ["pod_kernels.hip", "pod_probe.hip", "pod_planner.cpp", "pod_api.cpp"]
 HEADERS = ["pod_common.h", "pod_launch.h", "pod_planner.h", os.path.join("..", "..", "include", "pod_attn.h")]
 # Packed-fp32 instructions are switched off for the device pass (the host pass does not know
 # the feature and says so; that message is harmless).

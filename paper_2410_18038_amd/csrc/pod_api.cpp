@@ -79,6 +79,7 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.p_ratio = p.p_ratio;
     a.d_ratio = p.d_ratio;
     a.scale_log2 = p.prm.softmax_scale * 1.4426950408889634f;
+    a.trace = (pod::TraceRecord *)p.trace;
     return a;
 }
 
@@ -140,6 +141,16 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
     info->n_prefill_rows = p.n_prefill_rows;
     info->n_partial_rows = p.n_partial_rows;
     info->workspace_bytes = (int64_t)p.ws_bytes;
+    return POD_OK;
+}
+
+pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes)
+{
+    if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
+    const size_t need = (plan->p.pitems.size() + (size_t)plan->p.n_dwgs) * sizeof(pod::TraceRecord);
+    if (trace && trace_bytes < need) return fail(POD_ERR_WORKSPACE, "trace buffer too small");
+    plan->p.trace = trace;
+    plan->p.trace_bytes = trace ? trace_bytes : 0;
     return POD_OK;
 }
 

@@ -15,11 +15,15 @@ constexpr int kWgThreads = 256;            // 4 wavefronts per workgroup, one pe
 constexpr int kWavesPerWg = 4;
 constexpr int kPrefillRows = 128;          // packed (token, head-in-group) query rows per prefill item
 constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill step
-constexpr int kDecodeStep = 32;            // keys per decode step of one wavefront
+constexpr int kDecodeStep = 16;            // keys per decode step of one wavefront
 constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
 constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc << 6 | se << 4 | cu) < 1024
 
 enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
+
+// Cache layouts the kernels are specialised for: contiguous; paged with a block size that is a
+// multiple of 16 (a 16-key step then lies in one block, found with one scalar lookup); paged, any.
+enum Layout : int { kLayoutContiguous = 0, kLayoutPaged16 = 1, kLayoutPagedAny = 2 };
 
 // One prefill work item: a block of packed query rows of one K/V head over a key range.
 // Packed row R of a request stands for token R / group, query head kv_head * group + R % group,
@@ -76,6 +80,15 @@ POD_HD inline int role_for_arrival(uint32_t state, int p, int d)
     return (ticket % (p + d)) < p ? kPrefill : kDecode;
 }
 
+// Optional execution trace: where and when each workgroup of an attention kernel ran.
+struct TraceRecord {
+    int32_t cu;                            // hardware unit id (xcc << 6 | se << 4 | cu)
+    int32_t role;                          // kPrefill or kDecode
+    int32_t item;                          // prefill item id, or decode workgroup id
+    int32_t kernel;                        // LaunchKind of the kernel that wrote the record
+    uint64_t t_begin, t_end;               // constant-rate device clock (100 MHz)
+};
+
 // Everything a kernel needs; passed by value.
 struct KernelArgs {
     const void *prefill_q, *decode_q, *k_cache, *v_cache;
@@ -87,6 +100,7 @@ struct KernelArgs {
     float *part_o;                         // [n_partial_rows][d]  un-normalised fp32 output
     float *part_ml;                        // [n_partial_rows][2]  running max (log2 domain), weight sum
     WsHeader *hdr;
+    TraceRecord *trace;                    // optional: one record per workgroup of the attention kernels
     int64_t kv_seq_stride;
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;

@@ -25,6 +25,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define POD_LDS __attribute__((address_space(3)))
+#define POD_CONST __attribute__((address_space(4)))
 
 template <int DT> struct Num;
 template <> struct Num<0> {   // IEEE binary16
@@ -37,6 +38,10 @@ template <> struct Num<0> {   // IEEE binary16
     static __device__ __forceinline__ f32x4 mfma16(v8 a, v8 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
     }
+    // 16x16x16: `a` arrives as the raw result of an LDS transpose read
+    static __device__ __forceinline__ f32x4 mfma16k16(s16x4 a, v4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(v4, a), b, c, 0, 0, 0);
+    }
 };
 template <> struct Num<1> {   // bfloat16
     using v8 = bf16x8;
@@ -47,6 +52,9 @@ template <> struct Num<1> {   // bfloat16
     }
     static __device__ __forceinline__ f32x4 mfma16(v8 a, v8 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4 mfma16k16(s16x4 a, v4 b, f32x4 c) {
+        return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
     }
 };
 
@@ -85,6 +93,15 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+__device__ __forceinline__ void write_trace(const KernelArgs &a, int slot, int cu, int role, int item,
+                                            int kernel, uint64_t t0)
+{
+    TraceRecord r;
+    r.cu = cu; r.role = role; r.item = item; r.kernel = kernel;
+    r.t_begin = t0; r.t_end = wall_clock64();
+    a.trace[slot] = r;
+}
+
 __device__ __forceinline__ u32x4 load16(const void *p) { return *(const u32x4 *)p; }
 
 // ------------------------------------------------------------------------------------------
@@ -100,7 +117,7 @@ template <int D> struct PrefillLds {
     static constexpr int kBytes = kKBytes + kVBytes;
 };
 
-template <int DT, int D, bool PAGED>
+template <int DT, int D, int LAYOUT>
 __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const PrefillItem it,
                                                  unsigned char *smem)
 {
@@ -174,7 +191,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
             const int t = j0 + p * ROWS_PER_PASS + ld_row;
             u32x4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
             if (t < it.kv_end) {
-                const int64_t off = token_offset<PAGED>(a, cache_row, t, token_elems) + ld_chunk * 8;
+                const int64_t off = token_offset<LAYOUT != 0>(a, cache_row, t, token_elems) + ld_chunk * 8;
                 kz = load16(kc + off);
                 vz = load16(vc + off);
             }
@@ -303,10 +320,13 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 
 // ------------------------------------------------------------------------------------------
 // Decode path (Section 4.2.3: a decode workgroup is cut into one-wavefront virtual units, so
-// no workgroup barrier is used here).  A unit streams its K and V rows once, with fully
-// coalesced 16-byte loads, through a wavefront-private LDS region that only serves to turn the
-// rows into MFMA operands; the query heads of the group are the (zero padded) 16 columns, so
-// the matrix unit is busy for a few percent of the time (Section 4.2.1).
+// no workgroup barrier is used here).  A unit streams its K and V rows once from HBM with fully
+// coalesced 16-byte loads.  The rows of the next kRing-1 steps (16 keys each) are in flight in a
+// ring of registers, which is where the bytes-in-flight needed to cover HBM latency live: the
+// fused kernel's register budget is set by the prefill role, and the decode role spends it on
+// this ring.  A small wavefront-private LDS region only turns 16 rows at a time into MFMA
+// operands.  The query heads of the group are the (zero padded) 16 columns of the products, so
+// the matrix unit is busy for a few percent of the time only (Section 4.2.1).
 // ------------------------------------------------------------------------------------------
 template <int D> struct DecodeLds {
     static constexpr int kKStride = D * 2 + 16;
@@ -317,8 +337,13 @@ template <int D> struct DecodeLds {
     static constexpr int kBytes = kBytesPerWave * kWavesPerWg;
 };
 
-template <int DT, int D, bool PAGED>
-__device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const DecodeUnit u,
+template <int D> struct DecodeRing {
+    // registers per slot = D / 4 (K and V rows of 16 keys); about 160 registers of ring
+    static constexpr int kDepth = D == 128 ? 5 : 8;
+};
+
+template <int DT, int D, int LAYOUT>
+__device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int unit_index,
                                                 unsigned char *smem_wave)
 {
     using N = Num<DT>;
@@ -329,13 +354,22 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const Decod
     constexpr int CH = D / 8;                      // 16-byte chunks per row
     constexpr int RPI = kWaveSize / CH;            // rows per load instruction
     constexpr int NLD = kDecodeStep / RPI;         // load instructions per step, for K and for V
+    constexpr int R = DecodeRing<D>::kDepth;
+
+    // The unit descriptor and everything derived from it is wavefront-uniform: read it through
+    // the constant address space so that it lives in scalar registers.
+    DecodeUnit u;
+    {
+        const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.dunits + 8 * (int64_t)unit_index;
+        u.req = w[0]; u.kv_head = w[1]; u.t0 = w[2]; u.t1 = w[3]; u.prow0 = w[4]; u.split = w[5];
+        u.pad0 = 0; u.pad1 = 0;
+    }
+    const POD_CONST int32_t *meta = (const POD_CONST int32_t *)a.seq_meta + 4 * u.req;
+    const int q_start = meta[0], cache_row = meta[3];
 
     const int lane = threadIdx.x & 63;
     const int n16 = lane & 15;                     // query column (head within the group)
     const int b4 = lane >> 4;
-
-    const int32_t *meta = a.seq_meta + 4 * u.req;
-    const int q_start = meta[0], cache_row = meta[3];
     const int group = a.group;
     const int token_elems = a.n_kv_heads * D;
     const bool col_ok = n16 < group;
@@ -365,52 +399,68 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const Decod
     unsigned char *lds_v = smem_wave + L::kKBytes;
     const int ld_row = lane / CH, ld_chunk = lane % CH;
 
-    struct Stage { u32x4 k[NLD], v[NLD]; };
-    auto issue = [&](Stage &st, int t_base) {
-#pragma unroll
-        for (int p = 0; p < NLD; ++p) {
-            const int t = t_base + p * RPI + ld_row;
-            u32x4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
-            if (t < u.t1) {
-                const int64_t off = token_offset<PAGED>(a, cache_row, t, token_elems) + ld_chunk * 8;
-                kz = load16(kc + off);
-                vz = load16(vc + off);
-            }
-            st.k[p] = kz;
-            st.v[p] = vz;
+    const int n_steps = (u.t1 - u.t0 + kDecodeStep - 1) / kDecodeStep;
+    const POD_CONST int32_t *table = (const POD_CONST int32_t *)a.block_table +
+                                     (int64_t)cache_row * a.max_blocks_per_seq;
+
+    // All loads are unconditional so that the compiler's wait counters stay exact (a branch around
+    // a load makes it drain the whole ring): steps past the end re-read the last step and rows
+    // past the end re-read the last row; such keys are masked out of the softmax by their index.
+    const int t_last_step = u.t0 + (n_steps - 1) * kDecodeStep;
+
+    // Element offset of the first row of step `st` (LAYOUT 0 and 1: uniform; LAYOUT 2 handles rows itself).
+    auto step_base = [&](int st) -> int64_t {
+        const int t = min(u.t0 + st * kDecodeStep, t_last_step);
+        if constexpr (LAYOUT == kLayoutContiguous) {
+            return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
+        } else if constexpr (LAYOUT == kLayoutPaged16) {
+            // block_size is a multiple of 16 and t0 a multiple of 16: a step never straddles blocks
+            int bi, off;
+            if (a.bs_shift >= 0) { bi = t >> a.bs_shift; off = t & (a.block_size - 1); }
+            else { bi = t / a.block_size; off = t - bi * a.block_size; }
+            const int blk = table[bi];
+            return ((int64_t)blk * a.block_size + off) * token_elems;
+        } else {
+            return 0;
         }
     };
-    auto consume = [&](const Stage &st, int t_base) {
+
+    struct Slot { u32x4 k[NLD], v[NLD]; };
+    auto issue = [&](Slot &sl, int st, int64_t base) {
+        const int t_first = min(u.t0 + st * kDecodeStep, t_last_step);
+        const int last_row = u.t1 - 1 - t_first;             // >= 0
+#pragma unroll
+        for (int p = 0; p < NLD; ++p) {
+            const int row = min(p * RPI + ld_row, last_row);
+            int64_t off;
+            if constexpr (LAYOUT == kLayoutPagedAny)
+                off = token_offset<true>(a, cache_row, t_first + row, token_elems) + ld_chunk * 8;
+            else
+                off = base + (int64_t)row * token_elems + ld_chunk * 8;
+            sl.k[p] = load16(kc + off);
+            sl.v[p] = load16(vc + off);
+        }
+    };
+    auto consume = [&](const Slot &sl, int st) {
+        const int t_first = u.t0 + st * kDecodeStep;
 #pragma unroll
         for (int p = 0; p < NLD; ++p) {
             const int row = p * RPI + ld_row;
-            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = st.k[p];
-            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = st.v[p];
+            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = sl.k[p];
+            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = sl.v[p];
         }
         wave_lds_sync();                           // rows written by some lanes are read by others
-        // S^T tiles of 16 keys: register r of tile tt holds key t_base + tt*16 + 4*b4 + r.
-        f32x4 s[2];
+        // S^T tile: register r holds key t_first + 4*b4 + r of query column n16.
+        f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const v8 kk = *(const v8 *)(lds_k + (tt * 16 + n16) * L::kKStride + (ks * 32 + b4 * 8) * 2);
-                s[tt] = N::mfma16(kk, q[ks], s[tt]);
-            }
+        for (int ks = 0; ks < KS; ++ks) {
+            const v8 kk = *(const v8 *)(lds_k + n16 * L::kKStride + (ks * 32 + b4 * 8) * 2);
+            s = N::mfma16(kk, q[ks], s);
         }
-        if (t_base + kDecodeStep > u.t1) {
+        const int n_valid = u.t1 - t_first - 4 * b4;          // keys of this lane that exist
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (t_base + tt * 16 + 4 * b4 + r >= u.t1) s[tt][r] = neg_inf();
-        }
-        float mx = neg_inf();
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, s[tt][r]);
+        for (int r = 0; r < 4; ++r) s[r] = (r < n_valid) ? s[r] : neg_inf();
+        float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m_run, mx * c);
@@ -418,39 +468,47 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const Decod
         const float alpha = fast_exp2(m_run - m_use);
         m_run = m_new;
         float psum = 0.f;
-        v8 pk;
+        typename N::v4 pk;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float p = fast_exp2(__builtin_fmaf(s[tt][r], c, -m_use));
-                psum += p;
-                pk[tt * 4 + r] = (typename N::elem)p;
-            }
+        for (int r = 0; r < 4; ++r) {
+            const float p = fast_exp2(__builtin_fmaf(s[r], c, -m_use));
+            psum += p;
+            pk[r] = (typename N::elem)p;
+        }
         l_run = l_run * alpha + psum;
+        // O^T += V^T P^T over these 16 keys: lane's contraction slots 4*b4 + r are keys 4*b4 + r.
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
                                       (mb * 16 + (n16 & 3) * 4) * 2;
-            const s16x4 lo = lds_read_tr(vp);
-            const s16x4 hi = lds_read_tr(vp + 16 * L::kVStride);
-            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            const s16x4 vt = lds_read_tr(vp);
             o[mb] = o[mb] * alpha;
-            o[mb] = N::mfma16(__builtin_bit_cast(v8, both), pk, o[mb]);
+            o[mb] = N::mfma16k16(vt, pk, o[mb]);
         }
         wave_lds_sync();                           // all reads issued before the next step overwrites
     };
 
-    const int n_steps = (u.t1 - u.t0 + kDecodeStep - 1) / kDecodeStep;
-    Stage sa, sb;
-    if (n_steps > 0) issue(sa, u.t0);
-    for (int st = 0; st < n_steps; st += 2) {
-        const int t_base = u.t0 + st * kDecodeStep;
-        if (st + 1 < n_steps) issue(sb, t_base + kDecodeStep);
-        consume(sa, t_base);
-        if (st + 1 < n_steps) {
-            if (st + 2 < n_steps) issue(sa, t_base + 2 * kDecodeStep);
-            consume(sb, t_base + kDecodeStep);
+    // Ring of R slots: while step st is consumed, steps st+1 .. st+R-1 are in flight.
+    Slot ring[R];
+    int64_t next_base = step_base(0);
+#pragma unroll
+    for (int r = 0; r < R - 1; ++r) {
+        issue(ring[r], r, next_base);
+        __builtin_amdgcn_sched_barrier(0);         // loads return in issue order: keep oldest first
+        next_base = step_base(r + 1);
+    }
+    bool more = n_steps > 0;
+#pragma unroll 1
+    for (int base = 0; more; base += R) {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int st = base + r;
+            if (st >= n_steps) { more = false; break; }
+            issue(ring[(r + R - 1) % R], st + R - 1, next_base);
+            __builtin_amdgcn_sched_barrier(0);     // the new loads go out before this step's work
+            next_base = step_base(st + R);
+            consume(ring[r], st);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -489,21 +547,30 @@ template <int D> struct FusedLds {
 // ------------------------------------------------------------------------------------------
 // Stand-alone kernels: the in-house serial and two-stream baselines (Section 3.1).
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, bool PAGED>
+template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[PrefillLds<D>::kBytes];
-    prefill_item_run<DT, D, PAGED>(a, a.pitems[blockIdx.x], smem);
+    const uint64_t t0 = a.trace ? wall_clock64() : 0;
+    prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
+    if (a.trace && threadIdx.x == 0)
+        write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, blockIdx.x, kLaunchPrefill, t0);
 }
 
-template <int DT, int D, bool PAGED>
+template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[DecodeLds<D>::kBytes];
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int unit = blockIdx.x * kWavesPerWg + wave;
+    const uint64_t t0 = a.trace ? wall_clock64() : 0;
     if (unit < a.n_dunits)
-        decode_unit_run<DT, D, PAGED>(a, a.dunits[unit], smem + wave * DecodeLds<D>::kBytesPerWave);
+        decode_unit_run<DT, D, LAYOUT>(a, unit, smem + wave * DecodeLds<D>::kBytesPerWave);
+    if (a.trace) {
+        __syncthreads();
+        if (threadIdx.x == 0)
+            write_trace(a, a.n_pitems + blockIdx.x, __smid() & (kCuSlots - 1), kDecode, blockIdx.x, kLaunchDecode, t0);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -514,12 +581,13 @@ __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
 // operation when it is exhausted.  The sum of work ids equals the grid size, so every
 // workgroup ends up with exactly one item.
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, bool PAGED>
+template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[FusedLds<D>::kBytes];
     __shared__ int bind[4];
     WsHeader *hdr = a.hdr;
+    const uint64_t t0 = a.trace ? wall_clock64() : 0;
     if (threadIdx.x == 0) {
         const unsigned cu = __smid() & (kCuSlots - 1);
         const uint32_t state = atomicAdd(&hdr->cu_state[cu], kTicketOne);
@@ -540,15 +608,16 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     const int role = bind[0];
     const int id = bind[1];
     if (role == kPrefill) {
-        prefill_item_run<DT, D, PAGED>(a, a.pitems[id], smem);
+        prefill_item_run<DT, D, LAYOUT>(a, a.pitems[id], smem);
     } else if (role == kDecode) {
-        const int wave = threadIdx.x >> 6;
-        const int unit = id * kWavesPerWg + wave;
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        const int unit = __builtin_amdgcn_readfirstlane(id) * kWavesPerWg + wave;
         if (unit < a.n_dunits)
-            decode_unit_run<DT, D, PAGED>(a, a.dunits[unit], smem + wave * DecodeLds<D>::kBytesPerWave);
+            decode_unit_run<DT, D, LAYOUT>(a, unit, smem + wave * DecodeLds<D>::kBytesPerWave);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        if (a.trace) write_trace(a, blockIdx.x, bind[2], role, id, kLaunchFused, t0);
         if (role != kNone)
             atomicSub(&hdr->cu_state[bind[2]], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
         __threadfence();
@@ -627,21 +696,21 @@ __global__ void clear_header_kernel(WsHeader *hdr)
 // ------------------------------------------------------------------------------------------
 // Host-side launchers.
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, bool PAGED>
+template <int DT, int D, int LAYOUT>
 static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t stream)
 {
     switch (which) {
     case kLaunchPrefill:
         if (a.n_pitems > 0)
-            prefill_kernel<DT, D, PAGED><<<dim3(a.n_pitems), dim3(kWgThreads), 0, stream>>>(a);
+            prefill_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchDecode:
         if (a.n_dwgs > 0)
-            decode_kernel<DT, D, PAGED><<<dim3(a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+            decode_kernel<DT, D, LAYOUT><<<dim3(a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchFused:
         if (a.n_pitems + a.n_dwgs > 0)
-            fused_kernel<DT, D, PAGED><<<dim3(a.n_pitems + a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+            fused_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems + a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchCombine:
         if (a.n_combine > 0)
@@ -654,18 +723,24 @@ static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t str
 }
 
 template <int DT, int D>
-static hipError_t launch_layout(int which, const KernelArgs &a, bool paged, hipStream_t stream)
+static hipError_t launch_layout(int which, const KernelArgs &a, int layout, hipStream_t stream)
 {
-    return paged ? launch_variant<DT, D, true>(which, a, stream)
-                 : launch_variant<DT, D, false>(which, a, stream);
+    switch (layout) {
+    case kLayoutContiguous: return launch_variant<DT, D, kLayoutContiguous>(which, a, stream);
+    case kLayoutPaged16: return launch_variant<DT, D, kLayoutPaged16>(which, a, stream);
+    case kLayoutPagedAny: return launch_variant<DT, D, kLayoutPagedAny>(which, a, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
 {
-    if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, paged, stream);
-    if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, paged, stream);
-    if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, paged, stream);
-    if (dtype == 1 && head_dim == 64) return launch_layout<1, 64>(which, a, paged, stream);
+    const int layout = !paged ? kLayoutContiguous
+                              : (a.block_size % 16 == 0 ? kLayoutPaged16 : kLayoutPagedAny);
+    if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, layout, stream);
+    if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);
+    if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, layout, stream);
+    if (dtype == 1 && head_dim == 64) return launch_layout<1, 64>(which, a, layout, stream);
     return hipErrorInvalidValue;
 }
 

@@ -32,6 +32,8 @@ struct Plan {
     // side streams and events of the two-stream mode, created on first use
     void *side_stream[2] = {nullptr, nullptr};
     void *events[3] = {nullptr, nullptr, nullptr};
+    void *trace = nullptr;                  // device buffer for TraceRecords, or null
+    size_t trace_bytes = 0;
 };
 
 // Validates and fills `plan`; returns POD_OK or an error code with a message in `err`.

@@ -24,8 +24,9 @@ MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
 
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
-           "pod_attn_workspace_size", "pod_attn_plan_upload", "pod_attn_forward",
+           "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_upload", "pod_attn_forward",
            "pod_attn_simulate_binder", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
+           "pod_attn_probe_hbm_read", "pod_attn_probe_mfma",
            "pod_attn_last_error", "pod_attn_version"]
 
 
@@ -82,6 +83,8 @@ def lib():
         L.pod_attn_plan_destroy.argtypes = [vp]
         L.pod_attn_plan_info_get.restype = ctypes.c_int
         L.pod_attn_plan_info_get.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+        L.pod_attn_plan_set_trace.restype = ctypes.c_int
+        L.pod_attn_plan_set_trace.argtypes = [vp, vp, ctypes.c_size_t]
         L.pod_attn_workspace_size.restype = ctypes.c_size_t
         L.pod_attn_workspace_size.argtypes = [vp]
         L.pod_attn_plan_upload.restype = ctypes.c_int
@@ -96,6 +99,10 @@ def lib():
         L.pod_attn_plan_prefill_item.argtypes = [vp, ctypes.c_int32, i32p]
         L.pod_attn_plan_decode_unit.restype = ctypes.c_int
         L.pod_attn_plan_decode_unit.argtypes = [vp, ctypes.c_int32, i32p]
+        L.pod_attn_probe_hbm_read.restype = ctypes.c_int
+        L.pod_attn_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+        L.pod_attn_probe_mfma.restype = ctypes.c_int
+        L.pod_attn_probe_mfma.argtypes = [ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pod_attn_last_error.restype = ctypes.c_char_p
         L.pod_attn_version.restype = ctypes.c_char_p
         _lib = L
@@ -176,6 +183,14 @@ def pod_attn_plan_info_get(plan: Plan) -> PlanInfo:
     return info
 
 
+def pod_attn_plan_set_trace(plan: Plan, trace_ptr: int, trace_bytes: int):
+    _check(lib().pod_attn_plan_set_trace(plan.handle, ctypes.c_void_p(trace_ptr), trace_bytes))
+
+
+TRACE_DTYPE = np.dtype([("cu", np.int32), ("role", np.int32), ("item", np.int32), ("kernel", np.int32),
+                        ("t_begin", np.uint64), ("t_end", np.uint64)])
+
+
 def pod_attn_workspace_size(plan: Plan) -> int:
     return int(lib().pod_attn_workspace_size(plan.handle))
 
@@ -205,6 +220,22 @@ def pod_attn_forward(prefill_q: int, decode_q: int, k_cache: int, v_cache: int, 
     _check(lib().pod_attn_forward(vp(prefill_q), vp(decode_q), vp(k_cache), vp(v_cache), vp(seq_meta),
                                   vp(block_table), vp(out), plan.handle, vp(workspace), workspace_bytes,
                                   mode, vp(stream)))
+
+
+def pod_attn_probe_hbm_read(buf: int, nbytes: int, sink: int, stream: int = 0):
+    vp = ctypes.c_void_p
+    status = lib().pod_attn_probe_hbm_read(vp(buf), nbytes, vp(sink), vp(stream))
+    if status != POD_OK:
+        raise PodError(status, "pod_attn_probe_hbm_read failed")
+
+
+def pod_attn_probe_mfma(iters: int, sink: int, stream: int = 0) -> float:
+    """Enqueue the MFMA issue loop; returns the flop count of the launch."""
+    flops = ctypes.c_double(0.0)
+    status = lib().pod_attn_probe_mfma(iters, ctypes.c_void_p(sink), ctypes.byref(flops), ctypes.c_void_p(stream))
+    if status != POD_OK:
+        raise PodError(status, "pod_attn_probe_mfma failed")
+    return float(flops.value)
 
 
 def pod_attn_simulate_binder(n_prefill_items: int, n_decode_items: int, prefill_ratio: int,
@@ -263,6 +294,19 @@ class HybridAttention:
                          self.seq_meta_dev.data_ptr(), ptr(batch.block_table), out.data_ptr(), self.plan,
                          self.ws_ptr, self.ws_bytes, mode, stream)
         return out
+
+    def enable_trace(self):
+        """Allocate a trace buffer (one record per workgroup) and switch tracing on."""
+        n = max(self.info.fused_grid, 1)
+        self.trace = self.torch.zeros(n * 32, dtype=self.torch.uint8, device=self.workspace.device)
+        pod_attn_plan_set_trace(self.plan, self.trace.data_ptr(), self.trace.numel())
+
+    def read_trace(self) -> np.ndarray:
+        self.torch.cuda.synchronize()
+        return self.trace.cpu().numpy().view(TRACE_DTYPE)[: self.info.fused_grid].copy()
+
+    def disable_trace(self):
+        pod_attn_plan_set_trace(self.plan, 0, 0)
 
     def close(self):
         self.plan.close()

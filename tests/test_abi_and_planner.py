@@ -156,7 +156,7 @@ def coverage_check(prm, meta):
     # decode: token ranges tile [0, kv_len)
     ranges = {}
     for req, kvh, t0, t1, prow0, split, _, _ in units:
-        assert t0 % 32 == 0 and t0 < t1
+        assert t0 % 16 == 0 and t0 < t1
         ranges.setdefault((req, kvh), []).append((t0, t1, prow0))
     for r in range(prm.n_prefill, prm.n_prefill + prm.n_decode):
         for kvh in range(prm.n_kv_heads):
