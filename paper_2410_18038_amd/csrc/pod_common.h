@@ -21,8 +21,8 @@ constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc
 
 enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
 
-// Cache layouts the kernels are specialised for: contiguous; paged with a block size that is a
-// multiple of 16 (a 16-key step then lies in one block, found with one scalar lookup); paged, any.
+// Cache layouts the kernels are specialised for: contiguous; paged with a power-of-two block size
+// of at least 16 (a 16-key step then lies in one block, found with one scalar lookup); paged, any.
 enum Layout : int { kLayoutContiguous = 0, kLayoutPaged16 = 1, kLayoutPagedAny = 2 };
 
 // One prefill work item: a block of packed query rows of one K/V head over a key range.

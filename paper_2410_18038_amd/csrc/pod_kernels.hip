@@ -61,6 +61,35 @@ template <> struct Num<1> {   // bfloat16
 __device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Cross-lane reductions over the lanes that share a query column, with the gfx950 lane-swap
+// instructions (VALU speed, no LDS round trip).  permlane32_swap(x, x) yields {lower half twice,
+// upper half twice}; permlane16_swap(x, x) yields {even 16-lane rows twice, odd rows twice}.
+__device__ __forceinline__ float max_across_32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_32(float x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float max_across_16(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_across_16(float x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// The running maximum is only moved when a new score exceeds it by more than this many powers of
+// two; until then weights may reach 2^kMaxSlack, which 16-bit P and fp32 sums hold easily.  The
+// accumulators are then rescaled rarely instead of at every step.
+constexpr float kMaxSlack = 8.f;
+
 // LDS transpose read: within each group of 16 lanes, lane n receives element n of the four
 // 32-byte rows formed by the 8-byte pieces that lanes 4r..4r+3 point at (r = 0..3).
 __device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *p)
@@ -245,11 +274,18 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[tb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * c);
-        const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
+        mx = max_across_32(mx) * c;
+        const bool grow = mx > m_run + kMaxSlack;          // also true for the first visible key
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float alpha = grow ? fast_exp2(m_run - mx) : 1.f;   // mx is finite where grow holds
+            m_run = grow ? mx : m_run;
+            l_run *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+        }
+        const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
         float psum = 0.f;
         v8 pk[2][2];
 #pragma unroll
@@ -260,11 +296,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                 psum += p;
                 pk[tb][r >> 3][r & 7] = (typename N::elem)p;
             }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+        l_run += psum;
 
         // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
 #pragma unroll
@@ -285,7 +317,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     }
 
     // Epilogue.  o[mb][r] is channel mb*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_across_32(l_run);
     if (it.prow0 < 0) {
         if (row_ok) {
             const float inv = 1.f / l_tot;
@@ -337,9 +369,10 @@ template <int D> struct DecodeLds {
     static constexpr int kBytes = kBytesPerWave * kWavesPerWg;
 };
 
-template <int D> struct DecodeRing {
-    // registers per slot = D / 4 (K and V rows of 16 keys); about 160 registers of ring
-    static constexpr int kDepth = D == 128 ? 5 : 8;
+template <int D, int LAYOUT> struct DecodeRing {
+    // registers per slot = D / 4 (K and V rows of 16 keys); about 160 registers of ring.  The
+    // any-block-size layout needs per-lane 64-bit addresses and gets one slot less.
+    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 4 : 5) : 8;
 };
 
 template <int DT, int D, int LAYOUT>
@@ -354,7 +387,7 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
     constexpr int CH = D / 8;                      // 16-byte chunks per row
     constexpr int RPI = kWaveSize / CH;            // rows per load instruction
     constexpr int NLD = kDecodeStep / RPI;         // load instructions per step, for K and for V
-    constexpr int R = DecodeRing<D>::kDepth;
+    constexpr int R = DecodeRing<D, LAYOUT>::kDepth;
 
     // The unit descriptor and everything derived from it is wavefront-uniform: read it through
     // the constant address space so that it lives in scalar registers.
@@ -414,10 +447,8 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         if constexpr (LAYOUT == kLayoutContiguous) {
             return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
         } else if constexpr (LAYOUT == kLayoutPaged16) {
-            // block_size is a multiple of 16 and t0 a multiple of 16: a step never straddles blocks
-            int bi, off;
-            if (a.bs_shift >= 0) { bi = t >> a.bs_shift; off = t & (a.block_size - 1); }
-            else { bi = t / a.block_size; off = t - bi * a.block_size; }
+            // block_size is a power of two >= 16 and t0 a multiple of 16: a step never straddles blocks
+            const int bi = t >> a.bs_shift, off = t & (a.block_size - 1);
             const int blk = table[bi];
             return ((int64_t)blk * a.block_size + off) * token_elems;
         } else {
@@ -425,20 +456,42 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         }
     };
 
-    struct Slot { u32x4 k[NLD], v[NLD]; };
-    auto issue = [&](Slot &sl, int st, int64_t base) {
-        const int t_first = min(u.t0 + st * kDecodeStep, t_last_step);
-        const int last_row = u.t1 - 1 - t_first;             // >= 0
+    // Per-lane byte offsets inside a step, computed once: the step's base address is uniform and
+    // stays in scalar registers, so issuing a step costs no vector arithmetic.  The last step of
+    // the unit uses offsets clamped to its last existing row.
+    uint32_t voff_full[NLD], voff_tail[NLD];
+    {
+        const int last_row = u.t1 - 1 - t_last_step;          // 0..15
 #pragma unroll
         for (int p = 0; p < NLD; ++p) {
-            const int row = min(p * RPI + ld_row, last_row);
-            int64_t off;
-            if constexpr (LAYOUT == kLayoutPagedAny)
-                off = token_offset<true>(a, cache_row, t_first + row, token_elems) + ld_chunk * 8;
-            else
-                off = base + (int64_t)row * token_elems + ld_chunk * 8;
-            sl.k[p] = load16(kc + off);
-            sl.v[p] = load16(vc + off);
+            const int row = p * RPI + ld_row;
+            voff_full[p] = (uint32_t)(row * token_elems + ld_chunk * 8) * 2u;
+            voff_tail[p] = (uint32_t)(min(row, last_row) * token_elems + ld_chunk * 8) * 2u;
+        }
+    }
+
+    struct Slot { u32x4 k[NLD], v[NLD]; };
+    auto issue = [&](Slot &sl, int st, int64_t base) {
+        if constexpr (LAYOUT == kLayoutPagedAny) {
+            const int t_first = min(u.t0 + st * kDecodeStep, t_last_step);
+            const int last_row = u.t1 - 1 - t_first;         // >= 0
+#pragma unroll
+            for (int p = 0; p < NLD; ++p) {
+                const int row = min(p * RPI + ld_row, last_row);
+                const int64_t off = token_offset<true>(a, cache_row, t_first + row, token_elems) + ld_chunk * 8;
+                sl.k[p] = load16(kc + off);
+                sl.v[p] = load16(vc + off);
+            }
+        } else {
+            const bool tail = st >= n_steps - 1;              // uniform
+            const char *kb = (const char *)(kc + base);
+            const char *vb = (const char *)(vc + base);
+#pragma unroll
+            for (int p = 0; p < NLD; ++p) {
+                const uint32_t vo = tail ? voff_tail[p] : voff_full[p];
+                sl.k[p] = load16(kb + vo);
+                sl.v[p] = load16(vb + vo);
+            }
         }
     };
     auto consume = [&](const Slot &sl, int st) {
@@ -461,29 +514,29 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
 #pragma unroll
         for (int r = 0; r < 4; ++r) s[r] = (r < n_valid) ? s[r] : neg_inf();
         float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx * c);
-        const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
-        const float alpha = fast_exp2(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.f;
+        mx = max_across_32(max_across_16(mx)) * c;
+        const bool grow = mx > m_run + kMaxSlack;          // also true for the first key
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+            const float alpha = grow ? fast_exp2(m_run - mx) : 1.f;
+            m_run = grow ? mx : m_run;
+            l_run *= alpha;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) o[mb] = o[mb] * alpha;
+        }
+        const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
         typename N::v4 pk;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const float p = fast_exp2(__builtin_fmaf(s[r], c, -m_use));
-            psum += p;
+            l_run += p;
             pk[r] = (typename N::elem)p;
         }
-        l_run = l_run * alpha + psum;
         // O^T += V^T P^T over these 16 keys: lane's contraction slots 4*b4 + r are keys 4*b4 + r.
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
             const unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
                                       (mb * 16 + (n16 & 3) * 4) * 2;
-            const s16x4 vt = lds_read_tr(vp);
-            o[mb] = o[mb] * alpha;
-            o[mb] = N::mfma16k16(vt, pk, o[mb]);
+            o[mb] = N::mfma16k16(lds_read_tr(vp), pk, o[mb]);
         }
         wave_lds_sync();                           // all reads issued before the next step overwrites
     };
@@ -497,13 +550,14 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         __builtin_amdgcn_sched_barrier(0);         // loads return in issue order: keep oldest first
         next_base = step_base(r + 1);
     }
-    bool more = n_steps > 0;
+    // The body of a full turn of the ring is branch-free (a branch around a load would make the
+    // compiler's load counters drain the ring): a turn that runs past the last step consumes
+    // re-read rows whose keys are all masked by index, which changes nothing.
 #pragma unroll 1
-    for (int base = 0; more; base += R) {
+    for (int base = 0; base < n_steps; base += R) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int st = base + r;
-            if (st >= n_steps) { more = false; break; }
             issue(ring[(r + R - 1) % R], st + R - 1, next_base);
             __builtin_amdgcn_sched_barrier(0);     // the new loads go out before this step's work
             next_base = step_base(st + R);
@@ -513,8 +567,7 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
     }
 
     // o[mb][r] is channel mb*16 + 4*b4 + r of query column n16.
-    float l_tot = l_run + __shfl_xor(l_run, 16);
-    l_tot += __shfl_xor(l_tot, 32);
+    const float l_tot = sum_across_32(sum_across_16(l_run));
     if (!col_ok) return;
     if (u.prow0 < 0) {
         const float inv = 1.f / l_tot;
@@ -736,7 +789,7 @@ static hipError_t launch_layout(int which, const KernelArgs &a, int layout, hipS
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
 {
     const int layout = !paged ? kLayoutContiguous
-                              : (a.block_size % 16 == 0 ? kLayoutPaged16 : kLayoutPagedAny);
+                              : (a.bs_shift >= 4 ? kLayoutPaged16 : kLayoutPagedAny);
     if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, layout, stream);
     if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);
     if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, layout, stream);
