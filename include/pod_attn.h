@@ -103,7 +103,7 @@ typedef struct {
     int32_t decode_chunk;       /* tokens per decode unit actually chosen                        */
     int32_t prefill_ratio;      /* roles per compute unit, prefill : decode                      */
     int32_t decode_ratio;
-    int32_t fused_grid;         /* workgroups of the fused launch                                */
+    int32_t fused_grid;         /* workgroups of the fused launch (persistent, <= 2 per unit)    */
     int32_t n_compute_units;
     int64_t n_prefill_rows;     /* sum of q_len over prefill requests                            */
     int64_t n_partial_rows;     /* rows of fp32 partial output held in the workspace             */
@@ -134,12 +134,14 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
 
 /*
  * Optional execution trace, the evidence for co-location (Section 4.1 wants both operations
- * resident on every multiprocessor).  `trace` is device memory of at least 32 bytes per workgroup
- * of the fused launch (pod_attn_plan_info.fused_grid), or NULL to switch tracing off.  After a
- * forward call record w holds, as int32 {unit id, role (0 prefill / 1 decode), work id, kernel}
- * followed by two uint64 device timestamps (100 MHz) of the workgroup's begin and end.  The
- * fused kernel indexes records by workgroup; the stand-alone kernels by prefill item, then by
- * decode workgroup.  Tracing adds two clock reads and one 32-byte store per workgroup.
+ * resident on every multiprocessor).  `trace` is device memory of at least 48 bytes per workgroup
+ * of the largest launch (n_prefill_items + decode workgroups of the stand-alone kernels, which is
+ * never less than pod_attn_plan_info.fused_grid), or NULL to switch tracing off.  After a forward
+ * call, record w of the fused launch holds int32 {hardware unit id, first operation (0 prefill /
+ * 1 decode), work items done in the first operation, work items done after switching} followed by
+ * three uint64 device timestamps (100 MHz): begin, switch of operation, end, and 8 bytes of
+ * padding.  Prefill items are counted per workgroup, decode units per leading wavefront.  The
+ * stand-alone kernels write one record per prefill item, then one per decode workgroup.
  */
 pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes);
 

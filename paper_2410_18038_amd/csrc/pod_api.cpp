@@ -74,6 +74,7 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.n_pitems = (int)p.pitems.size();
     a.n_dunits = (int)p.dunits.size();
     a.n_dwgs = p.n_dwgs;
+    a.fused_grid = p.fused_grid;
     a.n_combine = (int)p.centries.size();
     a.n_prefill_rows = (int)p.n_prefill_rows;
     a.p_ratio = p.p_ratio;
@@ -136,7 +137,7 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
     info->decode_chunk = p.decode_chunk;
     info->prefill_ratio = p.p_ratio;
     info->decode_ratio = p.d_ratio;
-    info->fused_grid = (int32_t)p.pitems.size() + p.n_dwgs;
+    info->fused_grid = p.fused_grid;
     info->n_compute_units = p.n_cus;
     info->n_prefill_rows = p.n_prefill_rows;
     info->n_partial_rows = p.n_partial_rows;
@@ -147,7 +148,7 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
 pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes)
 {
     if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
-    const size_t need = (plan->p.pitems.size() + (size_t)plan->p.n_dwgs) * sizeof(pod::TraceRecord);
+    const size_t need = (plan->p.pitems.size() + (size_t)plan->p.n_dwgs) * sizeof(pod::TraceRecord);   // serial mode: one record per workgroup of either kernel
     if (trace && trace_bytes < need) return fail(POD_ERR_WORKSPACE, "trace buffer too small");
     plan->p.trace = trace;
     plan->p.trace_bytes = trace ? trace_bytes : 0;

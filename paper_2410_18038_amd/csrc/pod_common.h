@@ -57,9 +57,10 @@ struct WsHeader {
     // Per compute unit: bits 0-9 resident prefill workgroups, bits 10-19 resident decode
     // workgroups, bits 20-31 arrivals so far (the ticket of Section 4.1's listing).
     uint32_t cu_state[kCuSlots];
-    uint32_t next_item[2];                 // next work id per role
+    uint32_t next_item[2];                 // next prefill item id; next decode worker id
     uint32_t done;                         // workgroups that have finished
-    uint32_t pad[61];
+    uint32_t next_unit;                    // next decode unit id (claimed by wavefronts of decode workers)
+    uint32_t pad[60];
 };
 
 constexpr uint32_t kRunPrefillOne = 1u;
@@ -80,13 +81,14 @@ POD_HD inline int role_for_arrival(uint32_t state, int p, int d)
     return (ticket % (p + d)) < p ? kPrefill : kDecode;
 }
 
-// Optional execution trace: where and when each workgroup of an attention kernel ran.
+// Optional execution trace: where each workgroup of an attention kernel ran, which operation it
+// took first, when it switched to the other one and how many work items it processed in each.
 struct TraceRecord {
     int32_t cu;                            // hardware unit id (xcc << 6 | se << 4 | cu)
-    int32_t role;                          // kPrefill or kDecode
-    int32_t item;                          // prefill item id, or decode workgroup id
-    int32_t kernel;                        // LaunchKind of the kernel that wrote the record
-    uint64_t t_begin, t_end;               // constant-rate device clock (100 MHz)
+    int32_t first_role;                    // kPrefill or kDecode
+    int32_t n_first, n_second;             // items done in the first role, then in the other one
+    uint64_t t_begin, t_switch, t_end;     // constant-rate device clock (100 MHz)
+    uint64_t pad;
 };
 
 // Everything a kernel needs; passed by value.
@@ -105,8 +107,9 @@ struct KernelArgs {
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;
     int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1
-    int32_t n_pitems, n_dunits, n_dwgs, n_combine;
+    int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;
+    int32_t fused_grid;
     int32_t p_ratio, d_ratio;
     float scale_log2;                      // softmax_scale * log2(e)
 };

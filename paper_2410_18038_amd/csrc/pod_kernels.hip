@@ -122,12 +122,12 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__device__ __forceinline__ void write_trace(const KernelArgs &a, int slot, int cu, int role, int item,
-                                            int kernel, uint64_t t0)
+__device__ __forceinline__ void write_trace(const KernelArgs &a, int slot, int cu, int first_role,
+                                            int n_first, int n_second, uint64_t t0, uint64_t t_switch)
 {
     TraceRecord r;
-    r.cu = cu; r.role = role; r.item = item; r.kernel = kernel;
-    r.t_begin = t0; r.t_end = wall_clock64();
+    r.cu = cu; r.first_role = first_role; r.n_first = n_first; r.n_second = n_second;
+    r.t_begin = t0; r.t_switch = t_switch; r.t_end = wall_clock64(); r.pad = 0;
     a.trace[slot] = r;
 }
 
@@ -607,32 +607,91 @@ __global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
     prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
     if (a.trace && threadIdx.x == 0)
-        write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, blockIdx.x, kLaunchPrefill, t0);
+        write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
+}
+
+// A decode worker: each wavefront claims decode units from the shared counter until none is left
+// (the workgroup's four wavefronts are independent "virtual" units, Section 4.2.3).
+template <int DT, int D, int LAYOUT>
+__device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned char *smem)
+{
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    unsigned char *smem_wave = smem + wave * DecodeLds<D>::kBytesPerWave;
+    int n_done = 0;
+    for (;;) {
+        uint32_t unit = 0;
+        if ((threadIdx.x & 63) == 0) unit = atomicAdd(&a.hdr->next_unit, 1u);
+        unit = __builtin_amdgcn_readfirstlane(unit);
+        if (unit >= (uint32_t)a.n_dunits) break;
+        decode_unit_run<DT, D, LAYOUT>(a, (int)unit, smem_wave);
+        ++n_done;
+    }
+    return n_done;                                  // units done by this wavefront
+}
+
+// A prefill worker: the workgroup claims prefill items until none is left.
+template <int DT, int D, int LAYOUT>
+__device__ __forceinline__ int prefill_worker_run(const KernelArgs &a, unsigned char *smem, int *slot)
+{
+    int n_done = 0;
+    for (;;) {
+        __syncthreads();                            // previous item done with LDS and with *slot
+        if (threadIdx.x == 0) *slot = (int)atomicAdd(&a.hdr->next_item[kPrefill], 1u);
+        __syncthreads();
+        const int item = *slot;
+        if (item >= a.n_pitems) break;
+        prefill_item_run<DT, D, LAYOUT>(a, a.pitems[item], smem);
+        ++n_done;
+    }
+    return n_done;
+}
+
+// Last workgroup of a launch that used the counters leaves them at zero for the next launch.
+__device__ __forceinline__ void finish_and_reset(WsHeader *hdr, int *flag)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const uint32_t done = atomicAdd(&hdr->done, 1u);
+        *flag = (done == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (*flag) {
+        for (int i = threadIdx.x; i < kCuSlots; i += kWgThreads) hdr->cu_state[i] = 0u;
+        if (threadIdx.x == 0) {
+            hdr->next_item[0] = 0u;
+            hdr->next_item[1] = 0u;
+            hdr->next_unit = 0u;
+            hdr->done = 0u;
+        }
+    }
 }
 
 template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[DecodeLds<D>::kBytes];
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int unit = blockIdx.x * kWavesPerWg + wave;
+    __shared__ int flag;
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
-    if (unit < a.n_dunits)
-        decode_unit_run<DT, D, LAYOUT>(a, unit, smem + wave * DecodeLds<D>::kBytesPerWave);
+    const int n_done = decode_worker_run<DT, D, LAYOUT>(a, smem);
     if (a.trace) {
         __syncthreads();
         if (threadIdx.x == 0)
-            write_trace(a, a.n_pitems + blockIdx.x, __smid() & (kCuSlots - 1), kDecode, blockIdx.x, kLaunchDecode, t0);
+            write_trace(a, a.n_pitems + blockIdx.x, __smid() & (kCuSlots - 1), kDecode, n_done, 0, t0, wall_clock64());
     }
+    finish_and_reset(a.hdr, &flag);
 }
 
 // ------------------------------------------------------------------------------------------
-// Fused kernel: n_pitems + n_dwgs workgroups; each binds its operation after it has been
-// placed on a compute unit (Section 4.1).  The leader reads the hardware unit id, takes a
-// ticket from that unit's counter, chooses the operation that keeps the unit's resident mix
-// near the prefill:decode ratio, claims the next work id of that operation and switches
-// operation when it is exhausted.  The sum of work ids equals the grid size, so every
-// workgroup ends up with exactly one item.
+// Fused kernel.  One resident round of workgroups (two per compute unit); each binds its first
+// operation after it has been placed on a compute unit (Section 4.1): the leader reads the
+// hardware unit id, takes a ticket from that unit's counter and chooses the operation that keeps
+// the unit's resident mix at the prefill:decode ratio, so that every unit runs both at once.  A
+// workgroup then works as a persistent worker (Section 4.4): it claims work of its operation from
+// the shared counters until none is left, switches to the other operation (the listing's "switch
+// ops" step), and ends when both are exhausted.  As a prefill worker the whole workgroup takes
+// one item at a time; as a decode worker each of its wavefronts takes units on its own
+// (Section 4.2.3).  No workgroup ever waits for another one.
 // ------------------------------------------------------------------------------------------
 template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
@@ -644,48 +703,28 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     if (threadIdx.x == 0) {
         const unsigned cu = __smid() & (kCuSlots - 1);
         const uint32_t state = atomicAdd(&hdr->cu_state[cu], kTicketOne);
-        int role = role_for_arrival(state, a.p_ratio, a.d_ratio);
-        uint32_t id = atomicAdd(&hdr->next_item[role], 1u);
-        if (id >= (uint32_t)(role == kPrefill ? a.n_pitems : a.n_dwgs)) {
-            role ^= 1;
-            id = atomicAdd(&hdr->next_item[role], 1u);
-            if (id >= (uint32_t)(role == kPrefill ? a.n_pitems : a.n_dwgs)) role = kNone;
-        }
-        if (role != kNone)
-            atomicAdd(&hdr->cu_state[cu], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
+        const int role = role_for_arrival(state, a.p_ratio, a.d_ratio);
+        atomicAdd(&hdr->cu_state[cu], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
         bind[0] = role;
-        bind[1] = (int)id;
         bind[2] = (int)cu;
     }
     __syncthreads();
-    const int role = bind[0];
-    const int id = bind[1];
-    if (role == kPrefill) {
-        prefill_item_run<DT, D, LAYOUT>(a, a.pitems[id], smem);
-    } else if (role == kDecode) {
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        const int unit = __builtin_amdgcn_readfirstlane(id) * kWavesPerWg + wave;
-        if (unit < a.n_dunits)
-            decode_unit_run<DT, D, LAYOUT>(a, unit, smem + wave * DecodeLds<D>::kBytesPerWave);
+    const int first = bind[0];
+    int n_first, n_second;
+    uint64_t t_switch = 0;
+    if (first == kPrefill) {
+        n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
+        if (a.trace) t_switch = wall_clock64();
+        __syncthreads();
+        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem);
+    } else {
+        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem);
+        if (a.trace) t_switch = wall_clock64();
+        n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        if (a.trace) write_trace(a, blockIdx.x, bind[2], role, id, kLaunchFused, t0);
-        if (role != kNone)
-            atomicSub(&hdr->cu_state[bind[2]], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
-        __threadfence();
-        const uint32_t done = atomicAdd(&hdr->done, 1u);
-        bind[3] = (done == gridDim.x - 1) ? 1 : 0;
-    }
-    __syncthreads();
-    if (bind[3]) {                                  // last workgroup: leave the counters at zero
-        for (int i = threadIdx.x; i < kCuSlots; i += kWgThreads) hdr->cu_state[i] = 0u;
-        if (threadIdx.x == 0) {
-            hdr->next_item[0] = 0u;
-            hdr->next_item[1] = 0u;
-            hdr->done = 0u;
-        }
-    }
+    if (threadIdx.x == 0 && a.trace) write_trace(a, blockIdx.x, bind[2], first, n_first, n_second, t0, t_switch);
+    finish_and_reset(hdr, &bind[3]);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -762,8 +801,8 @@ static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t str
             decode_kernel<DT, D, LAYOUT><<<dim3(a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchFused:
-        if (a.n_pitems + a.n_dwgs > 0)
-            fused_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems + a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+        if (a.fused_grid > 0)
+            fused_kernel<DT, D, LAYOUT><<<dim3(a.fused_grid), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchCombine:
         if (a.n_combine > 0)

@@ -214,12 +214,17 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         std::stable_sort(plan.dunits.begin(), plan.dunits.end(), [](const DecodeUnit &x, const DecodeUnit &y) {
             return (x.t1 - x.t0) > (y.t1 - y.t0);
         });
-        plan.n_dwgs = ceil_div((int)plan.dunits.size(), kWavesPerWg);
+        // Decode workers are persistent: each of their wavefronts claims units until none is left.
+        // Two workgroups fit on a compute unit, so more workers than that would only queue.
+        plan.n_dwgs = std::min(2 * n_cus, ceil_div((int)plan.dunits.size(), kWavesPerWg));
     }
     if (next_prow > (int64_t)1 << 30) { err = "too many partial rows"; return POD_ERR_INVALID_ARG; }
     plan.n_partial_rows = next_prow;
 
     role_ratio(prm.policy, (int)plan.pitems.size(), plan.n_dwgs, plan.p_ratio, plan.d_ratio);
+    // The fused launch is one resident round of workgroups (two per compute unit) that loop over
+    // work, or fewer when the batch is smaller than that.
+    plan.fused_grid = std::min(2 * n_cus, (int)plan.pitems.size() + plan.n_dwgs);
 
     // ---- workspace layout --------------------------------------------------------------
     size_t off = align256(sizeof(WsHeader));

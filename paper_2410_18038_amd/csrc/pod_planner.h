@@ -25,7 +25,8 @@ struct Plan {
     int p_ratio = 1, d_ratio = 1;
     int decode_chunk = 0;
     int max_psplits = 1, max_dsplits = 1;
-    int n_dwgs = 0;
+    int n_dwgs = 0;                         // workgroups of the stand-alone decode kernel
+    int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)
     size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_part_o = 0, off_part_ml = 0;
     size_t ws_bytes = 0;

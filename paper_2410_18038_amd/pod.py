@@ -187,8 +187,8 @@ def pod_attn_plan_set_trace(plan: Plan, trace_ptr: int, trace_bytes: int):
     _check(lib().pod_attn_plan_set_trace(plan.handle, ctypes.c_void_p(trace_ptr), trace_bytes))
 
 
-TRACE_DTYPE = np.dtype([("cu", np.int32), ("role", np.int32), ("item", np.int32), ("kernel", np.int32),
-                        ("t_begin", np.uint64), ("t_end", np.uint64)])
+TRACE_DTYPE = np.dtype([("cu", np.int32), ("first_role", np.int32), ("n_first", np.int32), ("n_second", np.int32),
+                        ("t_begin", np.uint64), ("t_switch", np.uint64), ("t_end", np.uint64), ("pad", np.uint64)])
 
 
 def pod_attn_workspace_size(plan: Plan) -> int:
@@ -297,8 +297,8 @@ class HybridAttention:
 
     def enable_trace(self):
         """Allocate a trace buffer (one record per workgroup) and switch tracing on."""
-        n = max(self.info.fused_grid, 1)
-        self.trace = self.torch.zeros(n * 32, dtype=self.torch.uint8, device=self.workspace.device)
+        n = max(self.info.n_prefill_items + (self.info.n_decode_units + 3) // 4, self.info.fused_grid, 1)
+        self.trace = self.torch.zeros(n * 48, dtype=self.torch.uint8, device=self.workspace.device)
         pod_attn_plan_set_trace(self.plan, self.trace.data_ptr(), self.trace.numel())
 
     def read_trace(self) -> np.ndarray:
