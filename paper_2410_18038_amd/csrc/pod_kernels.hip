@@ -92,7 +92,7 @@ constexpr float kMaxSlack = 8.f;
 
 // LDS transpose read: within each group of 16 lanes, lane n receives element n of the four
 // 32-byte rows formed by the 8-byte pieces that lanes 4r..4r+3 point at (r = 0..3).
-__device__ __forceinline__ s16x4 lds_read_tr(const unsigned char *p)
+__device__ __forceinline__ s16x4 lds_read_tr(const POD_LDS unsigned char *p)
 {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((POD_LDS s16x4 *)p);
 }
@@ -135,16 +135,50 @@ __device__ __forceinline__ u32x4 load16(const void *p) { return *(const u32x4 *)
 
 // ------------------------------------------------------------------------------------------
 // Prefill path (Sections 2.1 and 4.3: the prefill operation as a device function that takes
-// its work id as a parameter).  One workgroup = 4 wavefronts x 32 packed query rows; K/V tiles
-// of 64 keys are staged through LDS once and read by all four wavefronts.
+// its work id as a parameter).  One workgroup = 4 wavefronts x 32 packed query rows.
+//
+// K/V tiles of 64 keys go from HBM/L2 straight into LDS (16-byte direct-to-LDS loads, no
+// register staging), double buffered, one workgroup barrier per tile.  A direct load writes a
+// wavefront's 64 chunks to consecutive LDS addresses, so rows cannot be padded; bank conflicts
+// are avoided instead by choosing WHICH 16-byte chunk of a row each lane fetches (an XOR
+// swizzle applied on the global side and undone by the readers).  The loop is software
+// pipelined: while the softmax of tile j runs on the vector ALUs, the matrix unit already
+// computes the scores of tile j+1, so K runs one tile ahead of V.
 // ------------------------------------------------------------------------------------------
 template <int D> struct PrefillLds {
-    static constexpr int kKStride = D * 2 + 16;    // bytes per K row: 4-bank skew between keys
-    static constexpr int kVStride = D * 2 + 64;    // bytes per V row: 16-bank skew for transpose reads
-    static constexpr int kKBytes = kPrefillKvTile * kKStride;
-    static constexpr int kVBytes = kPrefillKvTile * kVStride;
-    static constexpr int kBytes = kKBytes + kVBytes;
+    static constexpr int kRowBytes = D * 2;
+    static constexpr int kTileBytes = kPrefillKvTile * kRowBytes;
+    static constexpr int kBytes = 4 * kTileBytes;          // K[2] then V[2]
 };
+
+// Which chunk position of its LDS row a 16-byte chunk c of row `row` is stored at.
+template <int D> __device__ __forceinline__ int k_swizzle(int row, int c)
+{
+    return D == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+}
+template <int D> __device__ __forceinline__ int v_swizzle(int row, int c)
+{
+    return D == 128 ? (c ^ ((row & 3) << 2)) : (c ^ (((row >> 1) & 1) << 2));
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane i of the wavefront lands at
+// lds_addr + 16*i.  The global address is sbase + voff (uniform 64-bit base, 32-bit lane offset).
+// M0 carries the LDS address and is restored, since the compiler does not expect it to change.
+__device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const void *sbase)
+{
+    uint32_t saved;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+}
+__device__ __forceinline__ void dma16_vaddr(uint32_t lds_addr, const void *vaddr)
+{
+    uint32_t saved;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+                 "global_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved) : "s"(lds_addr), "v"(vaddr) : "memory");
+}
+__device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int DT, int D, int LAYOUT>
 __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const PrefillItem it,
@@ -156,18 +190,20 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     constexpr int KS = D / 16;                     // 16-channel slices of the QK^T contraction
     constexpr int MB = D / 32;                     // 32-channel blocks of the output
     constexpr int CH = D / 8;                      // 16-byte chunks per K/V row
-    constexpr int ROWS_PER_PASS = kWgThreads / CH;
-    constexpr int NPASS = kPrefillKvTile / ROWS_PER_PASS;
+    constexpr int RPW = kWaveSize / CH;            // rows one wavefront loads per pass (4 or 8)
+    constexpr int RPP = RPW * kWavesPerWg;         // rows per pass of the workgroup
+    constexpr int NPASS = kPrefillKvTile / RPP;
+    constexpr int T = kPrefillKvTile;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n32 = lane & 31;                     // query column owned by this lane
     const int h = lane >> 5;                       // which half of the contraction slots
     const int i16 = lane & 15;
     const int b16 = (lane >> 4) & 1;
 
-    const int32_t *meta = a.seq_meta + 4 * it.req;
+    const POD_CONST int32_t *meta = (const POD_CONST int32_t *)a.seq_meta + 4 * it.req;
     const int q_start = meta[0], q_len = meta[1], kv_len = meta[2], cache_row = meta[3];
     const int prefix = kv_len - q_len;
     const int group = a.group;
@@ -199,6 +235,78 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         }
     }
 
+    // ---- LDS addresses -----------------------------------------------------------------
+    // All LDS traffic goes through pointers in the LDS address space: K buffers at 0 and
+    // kTileBytes, V buffers at 2 and 3 times kTileBytes.
+    POD_LDS unsigned char *const lds = (POD_LDS unsigned char *)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;       // LDS byte address of the region
+    // readers: byte offsets inside a tile, without the compile-time row blocks
+    uint32_t k_rd[KS], v_rd[MB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        k_rd[ks] = (uint32_t)(n32 * L::kRowBytes + k_swizzle<D>(n32, 2 * ks + h) * 16);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+        const int row = 4 * h + (i16 >> 2);
+        const int c = mb * 4 + b16 * 2 + ((i16 & 3) >> 1);
+        v_rd[mb] = (uint32_t)(row * L::kRowBytes + v_swizzle<D>(row, c) * 16 + (i16 & 1) * 8);
+    }
+    // writers: this lane's LDS chunk in pass p is row p*RPP + wave*RPW + lane/CH, position lane%CH
+    const int wr_row = lane / CH, wr_pos = lane % CH;
+    uint32_t k_src[NPASS], v_src[NPASS];           // lane offsets in bytes for full tiles
+#pragma unroll
+    for (int p = 0; p < NPASS; ++p) {
+        const int row = p * RPP + wave * RPW + wr_row;
+        k_src[p] = (uint32_t)(wr_row * token_elems + k_swizzle<D>(row, wr_pos) * 8) * 2u;
+        v_src[p] = (uint32_t)(wr_row * token_elems + v_swizzle<D>(row, wr_pos) * 8) * 2u;
+    }
+
+    const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * D;
+    const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * D;
+    const POD_CONST int32_t *table = (const POD_CONST int32_t *)a.block_table +
+                                     (int64_t)cache_row * a.max_blocks_per_seq;
+    const int n_tiles = (it.kv_end - it.kv_begin + T - 1) / T;
+
+    // Issue the direct-to-LDS loads of one tile (K and/or V) into buffer `buf`.  Rows past the
+    // item's last key re-read its last row: finite data, masked out of the softmax by index.
+    auto issue_tile = [&](int jt, int buf, bool want_k, bool want_v) {
+        const int j0 = it.kv_begin + jt * T;
+        const int last_row = it.kv_end - 1 - j0;                // >= 0
+        const bool full = last_row >= T - 1;                    // uniform
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const int row_base = p * RPP + wave * RPW;           // uniform
+            const int base_eff = min(row_base, last_row & ~(RPW - 1));
+            const uint32_t dst_k = lds0 + (uint32_t)(buf * L::kTileBytes + (p * kWgThreads + wave * kWaveSize) * 16);
+            const uint32_t dst_v = dst_k + 2 * L::kTileBytes;
+            if constexpr (LAYOUT == kLayoutPagedAny) {
+                const int row = min(row_base + wr_row, last_row);
+                const int64_t off = token_offset<true>(a, cache_row, j0 + row, token_elems);
+                const int lrow = row_base + wr_row;              // swizzle follows the LDS row
+                if (want_k) dma16_vaddr(dst_k, kc + off + k_swizzle<D>(lrow, wr_pos) * 8);
+                if (want_v) dma16_vaddr(dst_v, vc + off + v_swizzle<D>(lrow, wr_pos) * 8);
+            } else {
+                const int t = j0 + base_eff;
+                int64_t base;
+                if constexpr (LAYOUT == kLayoutContiguous) {
+                    base = (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
+                } else {
+                    const int blk = table[t >> a.bs_shift];
+                    base = ((int64_t)blk * a.block_size + (t & (a.block_size - 1))) * token_elems;
+                }
+                uint32_t ko = k_src[p], vo = v_src[p];
+                if (!full) {
+                    const int lrow = row_base + wr_row;
+                    const int rl = min(lrow, last_row) - base_eff;
+                    ko = (uint32_t)(rl * token_elems + k_swizzle<D>(lrow, wr_pos) * 8) * 2u;
+                    vo = (uint32_t)(rl * token_elems + v_swizzle<D>(lrow, wr_pos) * 8) * 2u;
+                }
+                if (want_k) dma16(dst_k, ko, kc + base);
+                if (want_v) dma16(dst_v, vo, vc + base);
+            }
+        }
+    };
+
     f32x16 o[MB];
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -207,113 +315,103 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     float m_run = neg_inf(), l_run = 0.f;
     const float c = a.scale_log2;
 
-    const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * D;
-    const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * D;
-    unsigned char *lds_k = smem;
-    unsigned char *lds_v = smem + L::kKBytes;
-    const int ld_row = tid / CH, ld_chunk = tid % CH;
-
-    u32x4 kreg[NPASS], vreg[NPASS];
-    auto issue_loads = [&](int j0) {
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int t = j0 + p * ROWS_PER_PASS + ld_row;
-            u32x4 kz = {0u, 0u, 0u, 0u}, vz = {0u, 0u, 0u, 0u};
-            if (t < it.kv_end) {
-                const int64_t off = token_offset<LAYOUT != 0>(a, cache_row, t, token_elems) + ld_chunk * 8;
-                kz = load16(kc + off);
-                vz = load16(vc + off);
-            }
-            kreg[p] = kz;
-            vreg[p] = vz;
-        }
-    };
-
-    const int n_tiles = (it.kv_end - it.kv_begin + kPrefillKvTile - 1) / kPrefillKvTile;
-    if (n_tiles > 0) issue_loads(it.kv_begin);
-
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const int j0 = it.kv_begin + jt * kPrefillKvTile;
-        __syncthreads();                           // previous tile fully consumed
-#pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            const int row = p * ROWS_PER_PASS + ld_row;
-            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = kreg[p];
-            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = vreg[p];
-        }
-        __syncthreads();
-        if (jt + 1 < n_tiles) issue_loads(j0 + kPrefillKvTile);
-        if (j0 > wave_maxpos) continue;            // nothing visible to this wavefront
-
-        // S^T = K Q^T : rows = keys of the tile, columns = this wavefront's query rows.
-        f32x16 s[2];
+    // S^T = K Q^T for one tile: rows = keys, columns = this wavefront's query rows.
+    // Register r of block tb holds key j0 + tb*32 + 8*(r/4) + 4*h + r%4.
+    auto scores = [&](int kbuf, f32x16 (&s)[2]) {
+        const POD_LDS unsigned char *kb = lds + kbuf * L::kTileBytes;
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[tb][r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const v8 kk = *(const v8 *)(lds_k + (tb * 32 + n32) * L::kKStride + (ks * 16 + h * 8) * 2);
+                const v8 kk = *(const POD_LDS v8 *)(kb + tb * 32 * L::kRowBytes + k_rd[ks]);
                 s[tb] = N::mfma32(kk, q[ks], s[tb]);
             }
         }
-        // register r of block tb holds key j0 + tb*32 + 8*(r/4) + 4*h + r%4
-        const bool need_mask = (j0 + kPrefillKvTile - 1 > wave_minpos) || (j0 + kPrefillKvTile > it.kv_end);
-        if (need_mask) {
-            const int lim = min(pos, it.kv_end - 1);
+    };
+
+    if (n_tiles <= 0) return;                                // never planned; keeps the loop simple
+    __syncthreads();                                         // previous use of this LDS is over
+    issue_tile(0, 0, true, true);
+    if (n_tiles > 1) issue_tile(1, 1, true, false);
+    wait_all_loads();
+    __syncthreads();
+    f32x16 s_cur[2], s_next[2];
+    if (it.kv_begin <= wave_maxpos) scores(0, s_cur);
+    __syncthreads();                                         // K tile 0 is free to be overwritten
+
+    for (int jt = 0; jt < n_tiles; ++jt) {
+        const int j0 = it.kv_begin + jt * T;
+        const int cur = jt & 1;
+        // K tile jt was consumed in the previous iteration and V tile jt-1 as well (barrier below).
+        if (jt + 2 < n_tiles) issue_tile(jt + 2, cur, true, false);
+        if (jt + 1 < n_tiles) issue_tile(jt + 1, cur ^ 1, false, true);
+
+        const bool live = j0 <= wave_maxpos;                 // something visible to this wavefront
+        const bool next_live = (jt + 1 < n_tiles) && (j0 + T <= wave_maxpos);
+        if (next_live) scores(cur ^ 1, s_next);              // matrix unit: scores of the next tile
+        if (live) {
+            // vector ALUs: softmax of the current tile
+            const bool need_mask = (j0 + T - 1 > wave_minpos) || (j0 + T > it.kv_end);
+            if (__builtin_expect(need_mask, 0)) {
+                const int lim = min(pos, it.kv_end - 1);
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = j0 + tb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (key > lim) s_cur[tb][r] = neg_inf();
+                    }
+            }
+            float mx = neg_inf();
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[tb][r]);
+            mx = max_across_32(mx) * c;
+            const bool grow = mx > m_run + kMaxSlack;        // also true for the first visible key
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float alpha = grow ? fast_exp2(m_run - mx) : 1.f;   // mx is finite where grow holds
+                m_run = grow ? mx : m_run;
+                l_run *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
+            }
+            const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
+            float psum = 0.f;
+            v8 pk[2][2];
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int key = j0 + tb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                    if (key > lim) s[tb][r] = neg_inf();
+                    const float p = fast_exp2(__builtin_fmaf(s_cur[tb][r], c, -m_use));
+                    psum += p;
+                    pk[tb][r >> 3][r & 7] = (typename N::elem)p;
                 }
-        }
-        float mx = neg_inf();
+            l_run += psum;
+            // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
+            const POD_LDS unsigned char *vb = lds + (2 + cur) * L::kTileBytes;
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+            for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[tb][r]);
-        mx = max_across_32(mx) * c;
-        const bool grow = mx > m_run + kMaxSlack;          // also true for the first visible key
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-            const float alpha = grow ? fast_exp2(m_run - mx) : 1.f;   // mx is finite where grow holds
-            m_run = grow ? mx : m_run;
-            l_run *= alpha;
+                for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
-        }
-        const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
-        float psum = 0.f;
-        v8 pk[2][2];
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = fast_exp2(__builtin_fmaf(s[tb][r], c, -m_use));
-                psum += p;
-                pk[tb][r >> 3][r & 7] = (typename N::elem)p;
+                    for (int u = 0; u < 2; ++u) {
+                        const POD_LDS unsigned char *vp = vb + (tb * 32 + 16 * u) * L::kRowBytes + v_rd[mb];
+                        const s16x4 lo = lds_read_tr(vp);
+                        const s16x4 hi = lds_read_tr(vp + 8 * L::kRowBytes);
+                        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        o[mb] = N::mfma32(__builtin_bit_cast(v8, both), pk[tb][u], o[mb]);
+                    }
             }
-        l_run += psum;
-
-        // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int key0 = tb * 32 + 16 * u + 4 * h;
-                    const unsigned char *vp = lds_v + (key0 + (i16 >> 2)) * L::kVStride +
-                                              (mb * 32 + b16 * 16 + (i16 & 3) * 4) * 2;
-                    const s16x4 lo = lds_read_tr(vp);
-                    const s16x4 hi = lds_read_tr(vp + 8 * L::kVStride);
-                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[mb] = N::mfma32(__builtin_bit_cast(v8, both), pk[tb][u], o[mb]);
-                }
         }
+        wait_all_loads();                                    // K tile jt+2 and V tile jt+1 have landed
+        __syncthreads();                                     // ... for every wavefront; tile jt is done
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_next[tb];
     }
 
     // Epilogue.  o[mb][r] is channel mb*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
@@ -428,8 +526,8 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
 
     const typename N::elem *kc = (const typename N::elem *)a.k_cache + u.kv_head * D;
     const typename N::elem *vc = (const typename N::elem *)a.v_cache + u.kv_head * D;
-    unsigned char *lds_k = smem_wave;
-    unsigned char *lds_v = smem_wave + L::kKBytes;
+    POD_LDS unsigned char *const lds_k = (POD_LDS unsigned char *)smem_wave;
+    POD_LDS unsigned char *const lds_v = lds_k + L::kKBytes;
     const int ld_row = lane / CH, ld_chunk = lane % CH;
 
     const int n_steps = (u.t1 - u.t0 + kDecodeStep - 1) / kDecodeStep;
@@ -499,15 +597,15 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
 #pragma unroll
         for (int p = 0; p < NLD; ++p) {
             const int row = p * RPI + ld_row;
-            *(u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = sl.k[p];
-            *(u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = sl.v[p];
+            *(POD_LDS u32x4 *)(lds_k + row * L::kKStride + ld_chunk * 16) = sl.k[p];
+            *(POD_LDS u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = sl.v[p];
         }
         wave_lds_sync();                           // rows written by some lanes are read by others
         // S^T tile: register r holds key t_first + 4*b4 + r of query column n16.
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const v8 kk = *(const v8 *)(lds_k + n16 * L::kKStride + (ks * 32 + b4 * 8) * 2);
+            const v8 kk = *(const POD_LDS v8 *)(lds_k + n16 * L::kKStride + (ks * 32 + b4 * 8) * 2);
             s = N::mfma16(kk, q[ks], s);
         }
         const int n_valid = u.t1 - t_first - 4 * b4;          // keys of this lane that exist
@@ -534,7 +632,7 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         // O^T += V^T P^T over these 16 keys: lane's contraction slots 4*b4 + r are keys 4*b4 + r.
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
+            const POD_LDS unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
                                       (mb * 16 + (n16 & 3) * 4) * 2;
             o[mb] = N::mfma16k16(lds_read_tr(vp), pk, o[mb]);
         }
