@@ -14,7 +14,7 @@ HEADERS = ["pod_common.h", "pod_launch.h", "pod_planner.h", os.path.join("..", "
 # the feature and says so; that message is harmless).
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wall", "-Wno-unused-function"]
+               "-Wall", "-Wno-unused-function", "-Wno-inline-asm"]
 
 
 def hipcc() -> str:

@@ -22,7 +22,8 @@ constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc
 enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
 
 // Cache layouts the kernels are specialised for: contiguous; paged with a power-of-two block size
-// of at least 16 (a 16-key step then lies in one block, found with one scalar lookup); paged, any.
+// of at least 16 and a power-of-two number of bytes per token (a 16-key step then lies in one
+// block, found with one scalar lookup, and addresses need shifts only); paged, any.
 enum Layout : int { kLayoutContiguous = 0, kLayoutPaged16 = 1, kLayoutPagedAny = 2 };
 
 // One prefill work item: a block of packed query rows of one K/V head over a key range.
@@ -107,6 +108,7 @@ struct KernelArgs {
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;
     int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1
+    int32_t tok_shift;                     // log2(bytes per cached token = Hkv*d*2) when a power of two, else -1
     int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;
     int32_t fused_grid;

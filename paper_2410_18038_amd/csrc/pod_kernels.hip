@@ -42,6 +42,14 @@ template <> struct Num<0> {   // IEEE binary16
     static __device__ __forceinline__ f32x4 mfma16k16(s16x4 a, v4 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(v4, a), b, c, 0, 0, 0);
     }
+    // acc + sum of the eight 16-bit values (one dot-product instruction per pair)
+    static __device__ __forceinline__ float add_all(v8 p, float acc) {
+        typedef _Float16 v2 __attribute__((ext_vector_type(2)));
+        const v2 ones = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_fdot2(v2{p[2 * i], p[2 * i + 1]}, ones, acc, false);
+        return acc;
+    }
 };
 template <> struct Num<1> {   // bfloat16
     using v8 = bf16x8;
@@ -55,6 +63,13 @@ template <> struct Num<1> {   // bfloat16
     }
     static __device__ __forceinline__ f32x4 mfma16k16(s16x4 a, v4 b, f32x4 c) {
         return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ float add_all(v8 p, float acc) {
+        typedef __bf16 v2 __attribute__((ext_vector_type(2)));
+        const v2 ones = {(__bf16)1.f, (__bf16)1.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = __builtin_amdgcn_fdot2_f32_bf16(v2{p[2 * i], p[2 * i + 1]}, ones, acc, false);
+        return acc;
     }
 };
 
@@ -163,20 +178,17 @@ template <int D> __device__ __forceinline__ int v_swizzle(int row, int c)
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wavefront lands at
 // lds_addr + 16*i.  The global address is sbase + voff (uniform 64-bit base, 32-bit lane offset).
-// M0 carries the LDS address and is restored, since the compiler does not expect it to change.
+// M0 carries the LDS address.  These kernels use no other instruction that reads M0 (no GDS,
+// message, relative-move or interpolation instruction), so it is written without being restored.
 __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const void *sbase)
 {
-    uint32_t saved;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved) : "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_vaddr(uint32_t lds_addr, const void *vaddr)
 {
-    uint32_t saved;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-                 "global_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(saved) : "s"(lds_addr), "v"(vaddr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(vaddr) : "memory", "m0");
 }
 __device__ __forceinline__ void wait_all_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -251,14 +263,19 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         const int c = mb * 4 + b16 * 2 + ((i16 & 3) >> 1);
         v_rd[mb] = (uint32_t)(row * L::kRowBytes + v_swizzle<D>(row, c) * 16 + (i16 & 1) * 8);
     }
-    // writers: this lane's LDS chunk in pass p is row p*RPP + wave*RPW + lane/CH, position lane%CH
+    // writers: this lane's LDS chunk in pass p is row p*RPP + wave*RPW + lane/CH, position lane%CH.
+    // Lane offsets (bytes) of the source chunk for full tiles.  Contiguous cache: relative to the
+    // tile's first row.  Paged cache: relative to the first row of this wavefront's rows in the
+    // pass, which lie inside one block.
     const int wr_row = lane / CH, wr_pos = lane % CH;
-    uint32_t k_src[NPASS], v_src[NPASS];           // lane offsets in bytes for full tiles
+    const int tok_bytes = token_elems * 2;
+    uint32_t k_src[NPASS], v_src[NPASS];
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
         const int row = p * RPP + wave * RPW + wr_row;
-        k_src[p] = (uint32_t)(wr_row * token_elems + k_swizzle<D>(row, wr_pos) * 8) * 2u;
-        v_src[p] = (uint32_t)(wr_row * token_elems + v_swizzle<D>(row, wr_pos) * 8) * 2u;
+        const int src_row = LAYOUT == kLayoutContiguous ? row : wr_row;
+        k_src[p] = (uint32_t)(src_row * tok_bytes + k_swizzle<D>(row, wr_pos) * 16);
+        v_src[p] = (uint32_t)(src_row * tok_bytes + v_swizzle<D>(row, wr_pos) * 16);
     }
 
     const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * D;
@@ -267,12 +284,65 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                                      (int64_t)cache_row * a.max_blocks_per_seq;
     const int n_tiles = (it.kv_end - it.kv_begin + T - 1) / T;
 
-    // Issue the direct-to-LDS loads of one tile (K and/or V) into buffer `buf`.  Rows past the
+    // Byte offsets (from the start of the cache, K/V head 0) of the rows each pass of this
+    // wavefront loads, for a full tile: one uniform 64-bit value per pass.  For the paged layout
+    // the block ids come from the block table through scalar loads that are issued one tile
+    // earlier than they are needed (TileBlocks), so their latency is never waited for.
+    struct TileBases { int64_t b[NPASS]; };
+    struct TileBlocks { int32_t id[NPASS]; };
+    auto tile_blocks = [&](int jt) {
+        TileBlocks tb;
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            if constexpr (LAYOUT == kLayoutPaged16) {
+                const int t = min(it.kv_begin + jt * T + p * RPP + wave * RPW, it.kv_end - 1);
+                tb.id[p] = table[t >> a.bs_shift];
+            } else {
+                tb.id[p] = 0;
+            }
+        }
+        return tb;
+    };
+    auto tile_bases = [&](int jt, const TileBlocks &blk) {
+        TileBases tb;
+        const int j0 = it.kv_begin + jt * T;
+        if constexpr (LAYOUT == kLayoutContiguous) {
+            const int64_t off = ((int64_t)cache_row * a.kv_seq_stride + (int64_t)j0 * token_elems) * 2;
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) tb.b[p] = off;
+        } else if constexpr (LAYOUT == kLayoutPaged16) {
+            // block size and bytes per token are powers of two in this layout: shifts only
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) {
+                const uint32_t t = (uint32_t)(j0 + p * RPP + wave * RPW);
+                tb.b[p] = (int64_t)(((uint64_t)(uint32_t)blk.id[p] << (a.bs_shift + a.tok_shift)) +
+                                    (uint64_t)((t & (uint32_t)(a.block_size - 1)) << a.tok_shift));
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) tb.b[p] = 0;
+        }
+        return tb;
+    };
+    // Fast path for a full tile of the contiguous and power-of-two paged layouts.
+    auto issue_fast = [&](const TileBases &tb, int buf, bool is_k) {
+        const char *src = is_k ? (const char *)kc : (const char *)vc;
+#pragma unroll
+        for (int p = 0; p < NPASS; ++p) {
+            const uint32_t dst = lds0 + (uint32_t)((is_k ? buf : 2 + buf) * L::kTileBytes +
+                                                  (p * kWgThreads + wave * kWaveSize) * 16);
+            dma16(dst, is_k ? k_src[p] : v_src[p], src + tb.b[p]);
+        }
+    };
+    auto tile_is_fast = [&](int jt) {
+        return LAYOUT != kLayoutPagedAny && it.kv_end - (it.kv_begin + jt * T) >= T;
+    };
+
+    // General path: any layout, and the last tile of an item when it is not full.  Rows past the
     // item's last key re-read its last row: finite data, masked out of the softmax by index.
     auto issue_tile = [&](int jt, int buf, bool want_k, bool want_v) {
         const int j0 = it.kv_begin + jt * T;
         const int last_row = it.kv_end - 1 - j0;                // >= 0
-        const bool full = last_row >= T - 1;                    // uniform
 #pragma unroll
         for (int p = 0; p < NPASS; ++p) {
             const int row_base = p * RPP + wave * RPW;           // uniform
@@ -294,13 +364,10 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                     const int blk = table[t >> a.bs_shift];
                     base = ((int64_t)blk * a.block_size + (t & (a.block_size - 1))) * token_elems;
                 }
-                uint32_t ko = k_src[p], vo = v_src[p];
-                if (!full) {
-                    const int lrow = row_base + wr_row;
-                    const int rl = min(lrow, last_row) - base_eff;
-                    ko = (uint32_t)(rl * token_elems + k_swizzle<D>(lrow, wr_pos) * 8) * 2u;
-                    vo = (uint32_t)(rl * token_elems + v_swizzle<D>(lrow, wr_pos) * 8) * 2u;
-                }
+                const int lrow = row_base + wr_row;
+                const int rl = min(lrow, last_row) - base_eff;
+                const uint32_t ko = (uint32_t)(rl * token_elems + k_swizzle<D>(lrow, wr_pos) * 8) * 2u;
+                const uint32_t vo = (uint32_t)(rl * token_elems + v_swizzle<D>(lrow, wr_pos) * 8) * 2u;
                 if (want_k) dma16(dst_k, ko, kc + base);
                 if (want_v) dma16(dst_v, vo, vc + base);
             }
@@ -333,8 +400,23 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 
     if (n_tiles <= 0) return;                                // never planned; keeps the loop simple
     __syncthreads();                                         // previous use of this LDS is over
-    issue_tile(0, 0, true, true);
-    if (n_tiles > 1) issue_tile(1, 1, true, false);
+    TileBases carry = {};                                     // bases of tile jt+1 inside the loop
+    if (tile_is_fast(0)) {
+        const TileBases t0 = tile_bases(0, tile_blocks(0));
+        issue_fast(t0, 0, true);
+        issue_fast(t0, 0, false);
+    } else {
+        issue_tile(0, 0, true, true);
+    }
+    if (n_tiles > 1) {
+        if (tile_is_fast(1)) {
+            carry = tile_bases(1, tile_blocks(1));
+            issue_fast(carry, 1, true);
+        } else {
+            issue_tile(1, 1, true, false);
+        }
+    }
+    TileBlocks blocks_ahead = tile_blocks(2);                // for the K loads of the first iteration
     wait_all_loads();
     __syncthreads();
     f32x16 s_cur[2], s_next[2];
@@ -345,8 +427,21 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         const int j0 = it.kv_begin + jt * T;
         const int cur = jt & 1;
         // K tile jt was consumed in the previous iteration and V tile jt-1 as well (barrier below).
-        if (jt + 2 < n_tiles) issue_tile(jt + 2, cur, true, false);
-        if (jt + 1 < n_tiles) issue_tile(jt + 1, cur ^ 1, false, true);
+        TileBases fresh = carry;
+        if (jt + 2 < n_tiles) {
+            if (tile_is_fast(jt + 2)) {
+                fresh = tile_bases(jt + 2, blocks_ahead);
+                issue_fast(fresh, cur, true);
+            } else {
+                issue_tile(jt + 2, cur, true, false);
+            }
+        }
+        if (jt + 1 < n_tiles) {
+            if (tile_is_fast(jt + 1)) issue_fast(carry, cur ^ 1, false);
+            else issue_tile(jt + 1, cur ^ 1, false, true);
+        }
+        carry = fresh;
+        blocks_ahead = tile_blocks(jt + 3);                  // used by the next iteration
 
         const bool live = j0 <= wave_maxpos;                 // something visible to this wavefront
         const bool next_live = (jt + 1 < n_tiles) && (j0 + T <= wave_maxpos);
@@ -381,17 +476,17 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                     for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
             }
             const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
-            float psum = 0.f;
             v8 pk[2][2];
 #pragma unroll
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = fast_exp2(__builtin_fmaf(s_cur[tb][r], c, -m_use));
-                    psum += p;
-                    pk[tb][r >> 3][r & 7] = (typename N::elem)p;
-                }
-            l_run += psum;
+                for (int r = 0; r < 16; ++r)
+                    pk[tb][r >> 3][r & 7] = (typename N::elem)fast_exp2(__builtin_fmaf(s_cur[tb][r], c, -m_use));
+            // the weight sum is taken over the rounded weights, the ones the PV product uses
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) l_run = N::add_all(pk[tb][u], l_run);
             // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
             const POD_LDS unsigned char *vb = lds + (2 + cur) * L::kTileBytes;
 #pragma unroll
@@ -926,7 +1021,7 @@ static hipError_t launch_layout(int which, const KernelArgs &a, int layout, hipS
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
 {
     const int layout = !paged ? kLayoutContiguous
-                              : (a.bs_shift >= 4 ? kLayoutPaged16 : kLayoutPagedAny);
+                              : (a.bs_shift >= 4 && a.tok_shift >= 0 ? kLayoutPaged16 : kLayoutPagedAny);
     if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, layout, stream);
     if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);
     if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, layout, stream);
