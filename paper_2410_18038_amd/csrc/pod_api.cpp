@@ -1,6 +1,7 @@
 // C ABI of the library (see include/pod_attn.h).
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -84,6 +85,9 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.n_dunits = (int)p.dunits.size();
     a.n_dwgs = p.n_dwgs;
     a.fused_grid = p.fused_grid;
+    // About half of the fused launch starts in the decode operation; every workgroup takes a seat
+    // sooner or later, so all fixed units are run whatever the split turns out to be.
+    a.n_static_seats = std::min((p.fused_grid + 1) / 2, (int)(p.dunits.size() / pod::kWavesPerWg));
     a.n_combine = (int)p.centries.size();
     a.n_prefill_rows = (int)p.n_prefill_rows;
     a.p_ratio = p.p_ratio;

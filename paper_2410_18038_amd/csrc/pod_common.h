@@ -112,6 +112,7 @@ struct KernelArgs {
     int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;
     int32_t fused_grid;
+    int32_t n_static_seats;                // fused kernel: decode seats that start with four fixed units
     int32_t p_ratio, d_ratio;
     float scale_log2;                      // softmax_scale * log2(e)
 };

@@ -803,18 +803,33 @@ __global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
         write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
 }
 
-// A decode worker: each wavefront claims decode units from the shared counter until none is left
-// (the workgroup's four wavefronts are independent "virtual" units, Section 4.2.3).
+// A decode worker: each wavefront runs decode units until none is left (the workgroup's four
+// wavefronts are independent "virtual" units, Section 4.2.3).  Claims on one shared counter are
+// served one at a time by the memory system, and a chip-wide burst of them at the start of a
+// launch costs tens of microseconds.  So worker number `seat` (seats are handed out once per
+// workgroup) first takes the four units 4*seat .. 4*seat+3 without any counter when
+// seat < n_static_seats, and only then claims from the counter, which hands out the units from
+// 4*n_static_seats on.  (Issuing a claim early, before the previous unit's work, was tried and
+// is slower: loads return in order, so everything issued after a slow claim waits for it.)
 template <int DT, int D, int LAYOUT>
-__device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned char *smem)
+__device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned char *smem, int seat,
+                                                 int n_static_seats)
 {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     unsigned char *smem_wave = smem + wave * DecodeLds<D>::kBytesPerWave;
     int n_done = 0;
+    if (seat < n_static_seats) {
+        const int unit = seat * kWavesPerWg + wave;
+        if (unit < a.n_dunits) {
+            decode_unit_run<DT, D, LAYOUT>(a, unit, smem_wave);
+            ++n_done;
+        }
+    }
+    const uint32_t first_dynamic = (uint32_t)(n_static_seats * kWavesPerWg);
     for (;;) {
         uint32_t unit = 0;
         if ((threadIdx.x & 63) == 0) unit = atomicAdd(&a.hdr->next_unit, 1u);
-        unit = __builtin_amdgcn_readfirstlane(unit);
+        unit = __builtin_amdgcn_readfirstlane(unit) + first_dynamic;
         if (unit >= (uint32_t)a.n_dunits) break;
         decode_unit_run<DT, D, LAYOUT>(a, (int)unit, smem_wave);
         ++n_done;
@@ -866,7 +881,8 @@ __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
     __shared__ __attribute__((aligned(16))) unsigned char smem[DecodeLds<D>::kBytes];
     __shared__ int flag;
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
-    const int n_done = decode_worker_run<DT, D, LAYOUT>(a, smem);
+    // every workgroup of this kernel is a decode worker; its seat is its index
+    const int n_done = decode_worker_run<DT, D, LAYOUT>(a, smem, blockIdx.x, gridDim.x);
     if (a.trace) {
         __syncthreads();
         if (threadIdx.x == 0)
@@ -905,13 +921,23 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     const int first = bind[0];
     int n_first, n_second;
     uint64_t t_switch = 0;
+    // A workgroup takes its decode seat when it enters the decode operation, first or second.
+    auto take_seat = [&]() {
+        __syncthreads();
+        if (threadIdx.x == 0) bind[1] = (int)atomicAdd(&hdr->next_item[kDecode], 1u);
+        __syncthreads();
+        const int seat = bind[1];
+        __syncthreads();                                     // bind[1] is reused by the prefill worker
+        return seat;
+    };
     if (first == kPrefill) {
         n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
         if (a.trace) t_switch = wall_clock64();
-        __syncthreads();
-        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem);
+        const int seat = take_seat();
+        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
     } else {
-        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem);
+        const int seat = take_seat();
+        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
         if (a.trace) t_switch = wall_clock64();
         n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
     }
