@@ -74,7 +74,29 @@ def all_pairs(batch):
     return batch.visible_pairs() + int(batch.seq_meta[batch.n_prefill:, 2].sum())
 
 
-def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, pod, wl):
+def measure_peaks(torch, pod):
+    """What this GPU sustains: a coalesced 4 GiB read stream and a dense fp16 MFMA issue loop."""
+    buf = torch.empty(4 << 30, dtype=torch.uint8, device="cuda:0")
+    buf.zero_()
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda:0")
+    rd = lambda: pod.pod_attn_probe_hbm_read(buf.data_ptr(), buf.numel(), sink.data_ptr(),
+                                             torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        rd()
+    t_rd = float(np.median(event_times_us(rd, 10, torch)))
+    flops = [0.0]
+
+    def mf():
+        flops[0] = pod.pod_attn_probe_mfma(20000, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    for _ in range(2):
+        mf()
+    t_mf = float(np.median(event_times_us(mf, 5, torch)))
+    del buf
+    torch.cuda.empty_cache()
+    return {"hbm_read_GBps": (4 << 30) / t_rd / 1e3, "mfma_f16_TFLOPs": flops[0] / t_mf / 1e6}
+
+
+def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, pod, wl, peaks=None):
     dev = "cuda:0"
     t0 = time.time()
     batch = wl.config_batch(config, batch_index, device=dev)
@@ -195,6 +217,11 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         "speedup_vs_streams": results["streams"]["median_us"] / results["fused"]["median_us"],
         "modes": results, "max_abs_err_vs_oracle": max_err, "cpu_baseline": cpu,
     }
+    if peaks:
+        t_roof_meas = max(flops / (peaks["mfma_f16_TFLOPs"] * 1e12), kv_bytes / (peaks["hbm_read_GBps"] * 1e9)) * 1e6
+        rec["measured_peaks"] = peaks
+        rec["overlap_roofline_measured_peaks_us"] = t_roof_meas
+        rec["pct_of_overlap_roofline_measured_peaks"] = 100.0 * t_roof_meas / results[main_mode]["median_us"]
     attn.close()
     return rec
 
@@ -208,6 +235,10 @@ def main():
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the config-5 ratio sweep (0..11)")
     ap.add_argument("--mode", default="fused", choices=["fused", "serial", "streams"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the HBM-read and MFMA peak probes")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device copy and the 4 GiB read probe (known sizes, for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a profiler run) and exit")
     ap.add_argument("--sweep", default=None, help="also run every configuration and write the records to this file")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -221,9 +252,23 @@ def main():
         print("bench.py: no GPU visible; the attention path has no CPU fallback", file=sys.stderr)
         sys.exit(2)
     pod.lib()
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        src.zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        peaks = measure_peaks(torch, pod)
+        print(json.dumps({"copy_bytes": 1 << 30, "copies": 3, "read_probe_bytes": 4 << 30, "peaks": peaks}))
+        return
 
+    peaks = None if args.no_peaks else measure_peaks(torch, pod)
+    if peaks:
+        log(f"[bench] measured peaks: HBM read {peaks['hbm_read_GBps']:.0f} GB/s, "
+            f"fp16 MFMA {peaks['mfma_f16_TFLOPs']:.0f} TFLOP/s")
     rec = run_config(args.config, args.batch_index, args.steps, args.warmup, not args.no_cpu_baseline,
-                     args.mode, torch, pod, wl)
+                     args.mode, torch, pod, wl, peaks)
     log("[bench] modes (us, median/min/p90): " + json.dumps(rec["modes"]))
     if args.sweep:
         records = [rec]
@@ -231,7 +276,7 @@ def main():
         todo += [(5, i) for i in range(len(wl.RATIO_SWEEP)) if (5, i) != (args.config, args.batch_index)]
         for c, i in todo:
             torch.cuda.empty_cache()
-            r = run_config(c, i, args.steps, args.warmup, False, args.mode, torch, pod, wl)
+            r = run_config(c, i, args.steps, args.warmup, False, args.mode, torch, pod, wl, peaks)
             log(f"[bench] {r['config']['workload']}: fused {r['modes']['fused']['median_us']:.1f} us, "
                 f"serial {r['modes']['serial']['median_us']:.1f} us, streams {r['modes']['streams']['median_us']:.1f} us, "
                 f"{r['pct_of_overlap_roofline']:.1f}% of overlap roofline")

@@ -57,6 +57,8 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.pitems = (const pod::PrefillItem *)(ws + p.off_pitems);
     a.dunits = (const pod::DecodeUnit *)(ws + p.off_dunits);
     a.centries = (const pod::CombineEntry *)(ws + p.off_centries);
+    a.crows = (const int32_t *)(ws + p.off_crows);
+    a.n_crows = (int)(p.crows.size() / 2);
     a.part_o = (float *)(ws + p.off_part_o);
     a.part_ml = (float *)(ws + p.off_part_ml);
     a.kv_seq_stride = p.prm.kv_seq_stride;
@@ -202,10 +204,11 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
     hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
     if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
     struct Part { size_t off; const void *src; size_t bytes; };
-    const Part parts[3] = {
+    const Part parts[4] = {
         {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
         {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
-        {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)}};
+        {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)},
+        {p.off_crows, p.crows.data(), p.crows.size() * sizeof(int32_t)}};
     for (const Part &part : parts) {
         if (part.bytes == 0) continue;
         e = hipMemcpyAsync(ws + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s);
@@ -245,16 +248,12 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
         if (e == hipSuccess) e = pod::launch(which, args, dt, hd, paged, on);
     };
 
-    // The combine pass only touches groups whose partials were produced in this call.
+    // The combine pass only touches rows whose partials were produced in this call; the row list
+    // holds the rows of prefill groups first, then those of decode groups.
     pod::KernelArgs only_p = a, only_d = a;
-    {
-        // combine entries are stored prefill groups first, then decode groups
-        int n_pc = 0;
-        for (const pod::CombineEntry &c : p.centries) n_pc += (c.kind == pod::kPrefill);
-        only_p.n_combine = n_pc;
-        only_d.centries = a.centries + n_pc;
-        only_d.n_combine = a.n_combine - n_pc;
-    }
+    only_p.n_crows = p.n_crows_prefill;
+    only_d.crows = a.crows + 2 * (size_t)p.n_crows_prefill;
+    only_d.n_crows = a.n_crows - p.n_crows_prefill;
 
     switch (mode) {
     case POD_MODE_FUSED:

@@ -50,6 +50,8 @@ struct CombineEntry {
     int32_t kind;                          // kPrefill or kDecode
     int32_t req, kv_head, row0, n_rows;
     int32_t n_splits, prow0, split_stride; // partial row of split s, row r: prow0 + s*split_stride + r
+    int32_t q_start, q_len;                // copied from the request, so the merge needs no second lookup
+    int32_t pad0, pad1;
 };
 
 // Counters at the head of the device workspace.  All zero between launches: the last
@@ -100,6 +102,7 @@ struct KernelArgs {
     const PrefillItem *pitems;
     const DecodeUnit *dunits;
     const CombineEntry *centries;
+    const int32_t *crows;                  // [n_crows][2] = (combine entry, row inside it): one merged output row each
     float *part_o;                         // [n_partial_rows][d]  un-normalised fp32 output
     float *part_ml;                        // [n_partial_rows][2]  running max (log2 domain), weight sum
     WsHeader *hdr;
@@ -109,6 +112,7 @@ struct KernelArgs {
     int32_t block_size, max_blocks_per_seq;
     int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1
     int32_t tok_shift;                     // log2(bytes per cached token = Hkv*d*2) when a power of two, else -1
+    int32_t n_crows;
     int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;
     int32_t fused_grid;

@@ -273,7 +273,11 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 #pragma unroll
     for (int p = 0; p < NPASS; ++p) {
         const int row = p * RPP + wave * RPW + wr_row;
-        const int src_row = LAYOUT == kLayoutContiguous ? row : wr_row;
+        // contiguous: row inside the tile; paged: row inside the wavefront's rows of the pass, plus
+        // the wavefront's fixed row inside its block in the 16-key-block case
+        const int src_row = LAYOUT == kLayoutContiguous ? row
+                            : (LAYOUT == kLayoutPaged16 && D == 128 && a.bs_shift == 4 && a.max_blocks_per_seq >= 4)
+                                  ? wave * RPW + wr_row : wr_row;
         k_src[p] = (uint32_t)(src_row * tok_bytes + k_swizzle<D>(row, wr_pos) * 16);
         v_src[p] = (uint32_t)(src_row * tok_bytes + v_swizzle<D>(row, wr_pos) * 16);
     }
@@ -290,16 +294,29 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // earlier than they are needed (TileBlocks), so their latency is never waited for.
     struct TileBases { int64_t b[NPASS]; };
     struct TileBlocks { int32_t id[NPASS]; };
+    // With 16-key blocks and head_dim 128 a pass is exactly one block and the four ids of a tile
+    // are neighbours in the table: one 16-byte scalar load, and the wavefront's row offset inside
+    // its block never changes (it is folded into the lane offsets below).
+    typedef int32_t i32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+    const bool blocks16 = LAYOUT == kLayoutPaged16 && D == 128 && a.bs_shift == 4 && a.max_blocks_per_seq >= 4;
     auto tile_blocks = [&](int jt) {
         TileBlocks tb;
+        if constexpr (LAYOUT == kLayoutPaged16) {
+            if (D == 128 && blocks16) {
+                const int i0 = min((it.kv_begin + jt * T) >> 4, a.max_blocks_per_seq - 4);
+                const i32x4_a4 ids = *(const POD_CONST i32x4_a4 *)(table + i0);
 #pragma unroll
-        for (int p = 0; p < NPASS; ++p) {
-            if constexpr (LAYOUT == kLayoutPaged16) {
-                const int t = min(it.kv_begin + jt * T + p * RPP + wave * RPW, it.kv_end - 1);
-                tb.id[p] = table[t >> a.bs_shift];
+                for (int p = 0; p < NPASS; ++p) tb.id[p] = ids[p & 3];
             } else {
-                tb.id[p] = 0;
+#pragma unroll
+                for (int p = 0; p < NPASS; ++p) {
+                    const int t = min(it.kv_begin + jt * T + p * RPP + wave * RPW, it.kv_end - 1);
+                    tb.id[p] = table[t >> a.bs_shift];
+                }
             }
+        } else {
+#pragma unroll
+            for (int p = 0; p < NPASS; ++p) tb.id[p] = 0;
         }
         return tb;
     };
@@ -315,8 +332,9 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 const uint32_t t = (uint32_t)(j0 + p * RPP + wave * RPW);
-                tb.b[p] = (int64_t)(((uint64_t)(uint32_t)blk.id[p] << (a.bs_shift + a.tok_shift)) +
-                                    (uint64_t)((t & (uint32_t)(a.block_size - 1)) << a.tok_shift));
+                const uint64_t block_off = (uint64_t)(uint32_t)blk.id[p] << (a.bs_shift + a.tok_shift);
+                const uint64_t row_off = (uint64_t)((t & (uint32_t)(a.block_size - 1)) << a.tok_shift);
+                tb.b[p] = (int64_t)(blocks16 ? block_off : block_off + row_off);
             }
         } else {
 #pragma unroll
@@ -956,37 +974,54 @@ __global__ __launch_bounds__(kWgThreads) void combine_kernel(KernelArgs a)
     using N = Num<DT>;
     constexpr int TPR = D / 4;                      // threads per row, 4 channels each
     constexpr int RPP = kWgThreads / TPR;           // rows per pass
-    const CombineEntry e = a.centries[blockIdx.x];
-    const int32_t *meta = a.seq_meta + 4 * e.req;
-    const int q_start = meta[0], q_len = meta[1];
+    constexpr int U = 8;                            // splits fetched together (independent loads)
+    // every group of TPR threads merges one output row; a workgroup takes RPP rows of the list
     const int group = a.group;
     const int sub = threadIdx.x % TPR;
-    for (int r = threadIdx.x / TPR; r < e.n_rows; r += RPP) {
+    const int crow = blockIdx.x * RPP + threadIdx.x / TPR;
+    if (crow < a.n_crows) {
+        const int2 er = *(const int2 *)(a.crows + 2 * (int64_t)crow);
+        const CombineEntry e = a.centries[er.x];
+        const int r = er.y;
         int64_t out_row;
         int hq;
         if (e.kind == kPrefill) {
             const int R = e.row0 + r;
             const int tok = R / group;
-            if (tok >= q_len) continue;
             hq = e.kv_head * group + (R - tok * group);
-            out_row = q_start + tok;
+            out_row = e.q_start + tok;
         } else {
             hq = e.kv_head * group + r;
-            out_row = (int64_t)a.n_prefill_rows + q_start;
+            out_row = (int64_t)a.n_prefill_rows + e.q_start;
         }
-        float M = neg_inf();
-        for (int s = 0; s < e.n_splits; ++s)
-            M = fmaxf(M, a.part_ml[((int64_t)e.prow0 + (int64_t)s * e.split_stride + r) * 2]);
-        float lsum = 0.f;
+        float M = neg_inf(), lsum = 0.f;
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int s = 0; s < e.n_splits; ++s) {
-            const int64_t prow = (int64_t)e.prow0 + (int64_t)s * e.split_stride + r;
-            const float ms = a.part_ml[prow * 2];
-            if (ms == neg_inf()) continue;          // a split that saw no key of this row
-            const float w = fast_exp2(ms - M);
-            lsum += a.part_ml[prow * 2 + 1] * w;
-            const f32x4 v = *(const f32x4 *)(a.part_o + prow * D + sub * 4);
-            acc += v * w;
+        for (int s0 = 0; s0 < e.n_splits; s0 += U) {
+            float ms[U], ls[U];
+            f32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int s = min(s0 + u, e.n_splits - 1);
+                const int64_t prow = (int64_t)e.prow0 + (int64_t)s * e.split_stride + r;
+                const float2 ml = *(const float2 *)(a.part_ml + prow * 2);
+                ms[u] = (s0 + u < e.n_splits) ? ml.x : neg_inf();
+                ls[u] = ml.y;
+                v[u] = *(const f32x4 *)(a.part_o + prow * D + sub * 4);
+            }
+            float Mn = M;
+#pragma unroll
+            for (int u = 0; u < U; ++u) Mn = fmaxf(Mn, ms[u]);
+            if (Mn == neg_inf()) continue;          // no split so far saw a key of this row
+            const float keep = fast_exp2(M - Mn);   // 0 while M is still -inf
+            lsum *= keep;
+            acc = acc * keep;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float w = fast_exp2(ms[u] - Mn);   // 0 for a split that saw no key
+                lsum += ls[u] * w;
+                acc += v[u] * w;
+            }
+            M = Mn;
         }
         const float inv = 1.f / lsum;
         typename N::v4 w4;
@@ -1024,8 +1059,10 @@ static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t str
             fused_kernel<DT, D, LAYOUT><<<dim3(a.fused_grid), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchCombine:
-        if (a.n_combine > 0)
-            combine_kernel<DT, D><<<dim3(a.n_combine), dim3(kWgThreads), 0, stream>>>(a);
+        if (a.n_crows > 0) {
+            constexpr int kRowsPerWg = kWgThreads / (D / 4);
+            combine_kernel<DT, D><<<dim3((a.n_crows + kRowsPerWg - 1) / kRowsPerWg), dim3(kWgThreads), 0, stream>>>(a);
+        }
         break;
     default:
         return hipErrorInvalidValue;

@@ -154,7 +154,8 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
                         prow_base = next_prow;
                         next_prow += (int64_t)s * kPrefillRows;
                         plan.centries.push_back(CombineEntry{kPrefill, r, kvh, row0, n_rows, s,
-                                                             (int32_t)prow_base, kPrefillRows});
+                                                             (int32_t)prow_base, kPrefillRows,
+                                                             seq_meta[4 * r], q_len, 0, 0});
                     }
                     for (int i = 0; i < s; ++i) {
                         PrefillItem it;
@@ -180,10 +181,12 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         for (int r = prm.n_prefill; r < n_req; ++r) token_heads += (int64_t)seq_meta[4 * r + 2] * prm.n_kv_heads;
         int chunk = prm.decode_chunk;
         if (chunk <= 0) {
-            // Aim at about four units per resident wavefront slot so ragged contexts balance,
-            // but keep units long enough that their prologue and partial rows stay negligible.
+            // About two units per resident wavefront slot: ragged contexts still balance (units are
+            // claimed longest first), and units stay long enough (>= 512 keys) that their start-up
+            // (descriptor, Q, first K/V rows) and their partial rows stay small next to the stream.
             const int64_t slots = (int64_t)n_cus * 8;
-            chunk = (int)std::min<int64_t>(2048, std::max<int64_t>(256, (token_heads + 4 * slots - 1) / (4 * slots)));
+            chunk = (int)std::min<int64_t>(2048, std::max<int64_t>(512, (token_heads + 2 * slots - 1) / (2 * slots)));
+            chunk = round_up(chunk, 256);
         }
         chunk = round_up(std::max(chunk, kDecodeStep), kDecodeStep);
         plan.decode_chunk = chunk;
@@ -197,7 +200,8 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
                 if (s_eff > 1) {
                     prow_base = next_prow;
                     next_prow += (int64_t)s_eff * group;
-                    plan.centries.push_back(CombineEntry{kDecode, r, kvh, 0, group, s_eff, (int32_t)prow_base, group});
+                    plan.centries.push_back(CombineEntry{kDecode, r, kvh, 0, group, s_eff, (int32_t)prow_base, group,
+                                                         seq_meta[4 * r], 1, 0, 0});
                 }
                 for (int i = 0; i < s_eff; ++i) {
                     DecodeUnit u;
@@ -221,6 +225,17 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     if (next_prow > (int64_t)1 << 30) { err = "too many partial rows"; return POD_ERR_INVALID_ARG; }
     plan.n_partial_rows = next_prow;
 
+    // One (entry, row) pair per output row that is merged from partials, prefill entries first.
+    for (size_t e = 0; e < plan.centries.size(); ++e) {
+        const CombineEntry &c = plan.centries[e];
+        for (int r = 0; r < c.n_rows; ++r) {
+            if (c.kind == kPrefill && (c.row0 + r) / group >= c.q_len) continue;
+            plan.crows.push_back((int32_t)e);
+            plan.crows.push_back(r);
+        }
+        if (c.kind == kPrefill) plan.n_crows_prefill = (int)(plan.crows.size() / 2);
+    }
+
     role_ratio(prm.policy, (int)plan.pitems.size(), plan.n_dwgs, plan.p_ratio, plan.d_ratio);
     // The fused launch is one resident round of workgroups (two per compute unit) that loop over
     // work, or fewer when the batch is smaller than that.
@@ -231,6 +246,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     plan.off_pitems = off;   off = align256(off + plan.pitems.size() * sizeof(PrefillItem));
     plan.off_dunits = off;   off = align256(off + plan.dunits.size() * sizeof(DecodeUnit));
     plan.off_centries = off; off = align256(off + plan.centries.size() * sizeof(CombineEntry));
+    plan.off_crows = off;    off = align256(off + plan.crows.size() * sizeof(int32_t));
     plan.off_part_o = off;   off = align256(off + (size_t)plan.n_partial_rows * prm.head_dim * sizeof(float));
     plan.off_part_ml = off;  off = align256(off + (size_t)plan.n_partial_rows * 2 * sizeof(float));
     plan.ws_bytes = off;

@@ -20,6 +20,8 @@ struct Plan {
     std::vector<PrefillItem> pitems;
     std::vector<DecodeUnit> dunits;
     std::vector<CombineEntry> centries;
+    std::vector<int32_t> crows;             // (entry, row) pairs, prefill entries first
+    int n_crows_prefill = 0;
     int64_t n_prefill_rows = 0;
     int64_t n_partial_rows = 0;
     int p_ratio = 1, d_ratio = 1;
@@ -28,7 +30,7 @@ struct Plan {
     int n_dwgs = 0;                         // workgroups of the stand-alone decode kernel
     int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)
-    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_part_o = 0, off_part_ml = 0;
+    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_part_o = 0, off_part_ml = 0;
     size_t ws_bytes = 0;
     // side streams and events of the two-stream mode, created on first use
     void *side_stream[2] = {nullptr, nullptr};
