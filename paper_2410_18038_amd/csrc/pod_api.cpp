@@ -87,6 +87,7 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.n_dunits = (int)p.dunits.size();
     a.n_dwgs = p.n_dwgs;
     a.fused_grid = p.fused_grid;
+    for (int q = 0; q <= pod::kXcdQueues; ++q) a.pq_begin[q] = p.pq_begin[q];
     // About half of the fused launch starts in the decode operation; every workgroup takes a seat
     // sooner or later, so all fixed units are run whatever the split turns out to be.
     a.n_static_seats = std::min((p.fused_grid + 1) / 2, (int)(p.dunits.size() / pod::kWavesPerWg));

@@ -17,6 +17,7 @@ constexpr int kPrefillRows = 128;          // packed (token, head-in-group) quer
 constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill step
 constexpr int kDecodeStep = 16;            // keys per decode step of one wavefront
 constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
+constexpr int kXcdQueues = 8;               // prefill items are queued per XCD: one L2 per XCD
 constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc << 6 | se << 4 | cu) < 1024
 
 enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
@@ -63,7 +64,8 @@ struct WsHeader {
     uint32_t next_item[2];                 // next prefill item id; next decode worker id
     uint32_t done;                         // workgroups that have finished
     uint32_t next_unit;                    // next decode unit id (claimed by wavefronts of decode workers)
-    uint32_t pad[60];
+    uint32_t next_pitem_xcd[kXcdQueues];   // next prefill item of each per-XCD queue (offset inside the queue)
+    uint32_t pad[52];
 };
 
 constexpr uint32_t kRunPrefillOne = 1u;
@@ -116,6 +118,7 @@ struct KernelArgs {
     int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;
     int32_t fused_grid;
+    int32_t pq_begin[kXcdQueues + 1];      // prefill queue q holds items pq_begin[q] .. pq_begin[q+1]-1
     int32_t n_static_seats;                // fused kernel: decode seats that start with four fixed units
     int32_t p_ratio, d_ratio;
     float scale_log2;                      // softmax_scale * log2(e)

@@ -855,17 +855,33 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     return n_done;                                  // units done by this wavefront
 }
 
-// A prefill worker: the workgroup claims prefill items until none is left.
+// A prefill worker: the workgroup claims prefill items until none is left, first from the queue
+// of the XCD it runs on (the items of a K/V head sit in one queue, so their K/V tiles are re-read
+// from that XCD's L2), then from the other XCDs' queues.
 template <int DT, int D, int LAYOUT>
-__device__ __forceinline__ int prefill_worker_run(const KernelArgs &a, unsigned char *smem, int *slot)
+__device__ __forceinline__ int prefill_worker_run(const KernelArgs &a, unsigned char *smem, int *slot, int xcd)
 {
     int n_done = 0;
+    int q = xcd & (kXcdQueues - 1), tried = 0;
     for (;;) {
         __syncthreads();                            // previous item done with LDS and with *slot
-        if (threadIdx.x == 0) *slot = (int)atomicAdd(&a.hdr->next_item[kPrefill], 1u);
+        if (threadIdx.x == 0) {
+            int item = -1;
+            while (tried < kXcdQueues) {
+                const int len = a.pq_begin[q + 1] - a.pq_begin[q];
+                const int k = len > 0 ? (int)atomicAdd(&a.hdr->next_pitem_xcd[q], 1u) : len;
+                if (k < len) { item = a.pq_begin[q] + k; break; }
+                q = (q + 1) & (kXcdQueues - 1);     // this queue is empty for good: move on
+                ++tried;
+            }
+            slot[0] = item;
+            slot[1] = q | (tried << 8);
+        }
         __syncthreads();
-        const int item = *slot;
-        if (item >= a.n_pitems) break;
+        const int item = slot[0];
+        q = slot[1] & 255;
+        tried = slot[1] >> 8;
+        if (item < 0) break;
         prefill_item_run<DT, D, LAYOUT>(a, a.pitems[item], smem);
         ++n_done;
     }
@@ -889,6 +905,7 @@ __device__ __forceinline__ void finish_and_reset(WsHeader *hdr, int *flag)
             hdr->next_item[1] = 0u;
             hdr->next_unit = 0u;
             hdr->done = 0u;
+            for (int q = 0; q < kXcdQueues; ++q) hdr->next_pitem_xcd[q] = 0u;
         }
     }
 }
@@ -924,7 +941,7 @@ template <int DT, int D, int LAYOUT>
 __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[FusedLds<D>::kBytes];
-    __shared__ int bind[4];
+    __shared__ int bind[6];                                  // role, seat, unit id, last flag, item, queue
     WsHeader *hdr = a.hdr;
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
     if (threadIdx.x == 0) {
@@ -937,6 +954,7 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     }
     __syncthreads();
     const int first = bind[0];
+    const int xcd = bind[2] >> 6;                            // unit id = xcc << 6 | se << 4 | cu
     int n_first, n_second;
     uint64_t t_switch = 0;
     // A workgroup takes its decode seat when it enters the decode operation, first or second.
@@ -945,11 +963,10 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
         if (threadIdx.x == 0) bind[1] = (int)atomicAdd(&hdr->next_item[kDecode], 1u);
         __syncthreads();
         const int seat = bind[1];
-        __syncthreads();                                     // bind[1] is reused by the prefill worker
         return seat;
     };
     if (first == kPrefill) {
-        n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
+        n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
         if (a.trace) t_switch = wall_clock64();
         const int seat = take_seat();
         n_second = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
@@ -957,7 +974,7 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
         const int seat = take_seat();
         n_first = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
         if (a.trace) t_switch = wall_clock64();
-        n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[1]);
+        n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
     }
     __syncthreads();
     if (threadIdx.x == 0 && a.trace) write_trace(a, blockIdx.x, bind[2], first, n_first, n_second, t0, t_switch);

@@ -169,10 +169,21 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
                     plan.max_psplits = std::max(plan.max_psplits, s);
                 }
         }
-        // Longest first: work ids are claimed in order, so the long items start early.
-        std::stable_sort(plan.pitems.begin(), plan.pitems.end(), [](const PrefillItem &x, const PrefillItem &y) {
+        // One queue per XCD (each XCD has its own L2): items of one K/V head go to one queue, so
+        // the workgroups that re-read that head's K/V tiles share an L2 and the re-reads do not
+        // reach HBM.  Inside a queue: longest first, since ids are claimed in order.  A worker
+        // whose own queue is empty takes items from the other queues.
+        auto queue_of = [&](const PrefillItem &x) { return (x.req * prm.n_kv_heads + x.kv_head) % kXcdQueues; };
+        std::stable_sort(plan.pitems.begin(), plan.pitems.end(), [&](const PrefillItem &x, const PrefillItem &y) {
+            const int qx = queue_of(x), qy = queue_of(y);
+            if (qx != qy) return qx < qy;
             return (x.kv_end - x.kv_begin) > (y.kv_end - y.kv_begin);
         });
+        int at = 0;
+        for (int q = 0; q <= kXcdQueues; ++q) {
+            while (at < (int)plan.pitems.size() && queue_of(plan.pitems[(size_t)at]) < q) ++at;
+            plan.pq_begin[q] = q == kXcdQueues ? (int)plan.pitems.size() : at;
+        }
     }
 
     // ---- decode units ------------------------------------------------------------------

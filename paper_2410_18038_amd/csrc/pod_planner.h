@@ -27,6 +27,7 @@ struct Plan {
     int p_ratio = 1, d_ratio = 1;
     int decode_chunk = 0;
     int max_psplits = 1, max_dsplits = 1;
+    int pq_begin[kXcdQueues + 1] = {0};     // per-XCD prefill queues inside pitems
     int n_dwgs = 0;                         // workgroups of the stand-alone decode kernel
     int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)

@@ -174,9 +174,12 @@ def coverage_check(prm, meta):
     for a, b in zip(spans, spans[1:]):
         assert a[1] <= b[0]
     assert (spans[-1][1] if spans else 0) <= info.n_partial_rows
-    # longest-first ordering
-    lens = [i[5] - i[4] for i in items]
-    assert lens == sorted(lens, reverse=True)
+    # prefill items: one queue per XCD (K/V head modulo 8), queues in order, longest first inside a queue
+    queues = [int(i[0] * prm.n_kv_heads + i[1]) % 8 for i in items]
+    assert queues == sorted(queues)
+    for q in set(queues):
+        lens = [int(i[5] - i[4]) for i, qq in zip(items, queues) if qq == q]
+        assert lens == sorted(lens, reverse=True)
     lens = [u[3] - u[2] for u in units]
     assert lens == sorted(lens, reverse=True)
     assert pod.pod_attn_workspace_size(plan) == info.workspace_bytes >= 4352
