@@ -145,6 +145,18 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
  */
 pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes);
 
+/*
+ * Optional event log: when each prefill item and each decode unit ran, the evidence for how the
+ * two operations overlap in time inside one launch (Section 4.1, Section 5.1).  `log` is 16-byte
+ * aligned device memory, or NULL to switch logging off: a 16-byte header whose first uint32 counts
+ * the records appended (the caller zeroes it before a forward call), then 32-byte records
+ * {int32 kind (0 prefill / 1 decode), int32 item or unit index, int32 hardware unit id,
+ * int32 workgroup * 4 + wavefront, uint64 begin, uint64 end} (100 MHz device clock).  Records
+ * beyond the capacity (log_bytes - 16) / 32 are counted, not stored.  Logging costs one atomic
+ * per item; timings taken with it on are slightly slower.
+ */
+pod_status pod_attn_plan_set_event_log(pod_attn_plan *plan, void *log, size_t log_bytes);
+
 /* Bytes of device workspace the plan needs (work tables, counters, split partials). */
 size_t     pod_attn_workspace_size(const pod_attn_plan *plan);
 
@@ -209,11 +221,22 @@ int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items
  *   prefill item: {request, kv_head, first packed row, n packed rows, kv_begin, kv_end,
  *                  first partial row or -1, split index}
  *   decode unit : {request, kv_head, token_begin, token_end, first partial row or -1,
- *                  split index, 0, 0}
+ *                  split index, first query row of the request, cache row of the request}
  * Returns POD_ERR_INVALID_ARG when index is out of range.
  */
 pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
 pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
+
+/*
+ * How the decode units are handed out (host, for tests).  Units [0, begin of queue 0) are the fixed
+ * first units of the decode workers: worker w's wavefront v starts with unit 4*w + v and claims
+ * nothing for it.  Every other unit sits in one of 8 queues, one per XCD; queue q holds units
+ * [*begin, *end), and a wavefront claims from the queue of the XCD it runs on before it tries the
+ * others (the virtual decode CTAs of Section 4.2.3 are these units; which multiprocessor runs
+ * which of them is decided at run time as in Section 4.1).  Units are sorted longest first inside
+ * the fixed range and inside each queue.  Returns POD_ERR_INVALID_ARG when q is not in 0..7.
+ */
+pod_status pod_attn_plan_decode_queue(const pod_attn_plan *plan, int32_t q, int32_t *begin, int32_t *end);
 
 /*
  * Measurement aids (Section 5.1 reports compute and bandwidth utilisation; these give the two

@@ -88,15 +88,18 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.n_dwgs = p.n_dwgs;
     a.fused_grid = p.fused_grid;
     for (int q = 0; q <= pod::kXcdQueues; ++q) a.pq_begin[q] = p.pq_begin[q];
-    // About half of the fused launch starts in the decode operation; every workgroup takes a seat
-    // sooner or later, so all fixed units are run whatever the split turns out to be.
-    a.n_static_seats = std::min((p.fused_grid + 1) / 2, (int)(p.dunits.size() / pod::kWavesPerWg));
+    // Every workgroup of a launch with decode work takes a decode seat sooner or later, so all
+    // fixed units are run whatever operation the workgroups start with.
+    a.dq_begin = (const int32_t *)(ws + p.off_dq);
+    a.n_static_seats = p.n_static_seats;
     a.n_combine = (int)p.centries.size();
     a.n_prefill_rows = (int)p.n_prefill_rows;
     a.p_ratio = p.p_ratio;
     a.d_ratio = p.d_ratio;
     a.scale_log2 = p.prm.softmax_scale * 1.4426950408889634f;
     a.trace = (pod::TraceRecord *)p.trace;
+    a.evlog = (uint32_t *)p.evlog;
+    a.evlog_cap = p.evlog ? (uint32_t)((p.evlog_bytes - 16) / sizeof(pod::EventRecord)) : 0u;
     return a;
 }
 
@@ -171,6 +174,16 @@ pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trac
     return POD_OK;
 }
 
+pod_status pod_attn_plan_set_event_log(pod_attn_plan *plan, void *log, size_t log_bytes)
+{
+    if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
+    if (log && log_bytes < 16 + sizeof(pod::EventRecord)) return fail(POD_ERR_WORKSPACE, "event log too small");
+    if (log && ((uintptr_t)log & 15)) return fail(POD_ERR_INVALID_ARG, "event log must be 16-byte aligned");
+    plan->p.evlog = log;
+    plan->p.evlog_bytes = log ? log_bytes : 0;
+    return POD_OK;
+}
+
 size_t pod_attn_workspace_size(const pod_attn_plan *plan) { return plan ? plan->p.ws_bytes : 0; }
 
 pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8])
@@ -188,8 +201,17 @@ pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, i
     if (!plan || !out || index < 0 || index >= (int32_t)plan->p.dunits.size())
         return fail(POD_ERR_INVALID_ARG, "decode unit index out of range");
     const pod::DecodeUnit &u = plan->p.dunits[(size_t)index];
-    const int32_t v[8] = {u.req, u.kv_head, u.t0, u.t1, u.prow0, u.split, 0, 0};
+    const int32_t v[8] = {u.req, u.kv_head, u.t0, u.t1, u.prow0, u.split, u.q_start, u.cache_row};
     std::memcpy(out, v, sizeof v);
+    return POD_OK;
+}
+
+pod_status pod_attn_plan_decode_queue(const pod_attn_plan *plan, int32_t q, int32_t *begin, int32_t *end)
+{
+    if (!plan || !begin || !end || q < 0 || q >= pod::kXcdQueues)
+        return fail(POD_ERR_INVALID_ARG, "decode queue index out of range");
+    *begin = plan->p.dq_begin[q];
+    *end = plan->p.dq_begin[q + 1];
     return POD_OK;
 }
 
@@ -205,7 +227,8 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
     hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
     if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
     struct Part { size_t off; const void *src; size_t bytes; };
-    const Part parts[4] = {
+    const Part parts[5] = {
+        {p.off_dq, p.dq_begin, sizeof p.dq_begin},
         {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
         {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
         {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)},

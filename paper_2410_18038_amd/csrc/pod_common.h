@@ -17,7 +17,8 @@ constexpr int kPrefillRows = 128;          // packed (token, head-in-group) quer
 constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill step
 constexpr int kDecodeStep = 16;            // keys per decode step of one wavefront
 constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
-constexpr int kXcdQueues = 8;               // prefill items are queued per XCD: one L2 per XCD
+constexpr int kXcdQueues = 8;               // work is queued per XCD (one L2 each); a queue's counter is claimed mostly from its own XCD
+constexpr int kNullClaimLines = 512;       // power of two, at least the number of resident workgroups
 constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc << 6 | se << 4 | cu) < 1024
 
 enum Role : int { kPrefill = 0, kDecode = 1, kNone = -1 };
@@ -43,7 +44,8 @@ struct PrefillItem {
 struct DecodeUnit {
     int32_t req, kv_head, t0, t1;
     int32_t prow0;                         // first partial row (group rows), or -1
-    int32_t split, pad0, pad1;
+    int32_t split;
+    int32_t q_start, cache_row;            // copied from the request: a unit starts with one lookup
 };
 
 // One group of output rows merged from split partials.
@@ -63,9 +65,15 @@ struct WsHeader {
     uint32_t cu_state[kCuSlots];
     uint32_t next_item[2];                 // next prefill item id; next decode worker id
     uint32_t done;                         // workgroups that have finished
-    uint32_t next_unit;                    // next decode unit id (claimed by wavefronts of decode workers)
+    uint32_t pad0;
     uint32_t next_pitem_xcd[kXcdQueues];   // next prefill item of each per-XCD queue (offset inside the queue)
     uint32_t pad[52];
+    // Next decode unit of each per-XCD queue (offset inside the queue), claimed by wavefronts.
+    // One 128-byte line per counter, so the eight hot words are served by different channels.
+    uint32_t next_dunit_xcd[kXcdQueues][32];
+    // Words that decode wavefronts add zero to in the turns in which they claim nothing (one
+    // line per workgroup; see the decode worker).  Always zero.
+    uint32_t null_claim[kNullClaimLines][32];
 };
 
 constexpr uint32_t kRunPrefillOne = 1u;
@@ -96,6 +104,17 @@ struct TraceRecord {
     uint64_t pad;
 };
 
+// Optional event log: one record per prefill item (written by the workgroup) and per decode unit
+// (written by the wavefront).  The log starts with a 16-byte header whose first word counts the
+// records appended so far; records beyond the capacity are counted but not stored.
+struct EventRecord {
+    int32_t kind;                          // kPrefill or kDecode
+    int32_t item;                          // prefill item or decode unit index
+    int32_t cu;                            // hardware unit id
+    int32_t wg;                            // workgroup index * 4 + wavefront
+    uint64_t t_begin, t_end;               // constant-rate device clock (100 MHz)
+};
+
 // Everything a kernel needs; passed by value.
 struct KernelArgs {
     const void *prefill_q, *decode_q, *k_cache, *v_cache;
@@ -109,6 +128,8 @@ struct KernelArgs {
     float *part_ml;                        // [n_partial_rows][2]  running max (log2 domain), weight sum
     WsHeader *hdr;
     TraceRecord *trace;                    // optional: one record per workgroup of the attention kernels
+    uint32_t *evlog;                       // optional: event log (16-byte header, then EventRecords)
+    uint32_t evlog_cap;                    // records the event log can hold
     int64_t kv_seq_stride;
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;
@@ -119,7 +140,8 @@ struct KernelArgs {
     int32_t n_prefill_rows;
     int32_t fused_grid;
     int32_t pq_begin[kXcdQueues + 1];      // prefill queue q holds items pq_begin[q] .. pq_begin[q+1]-1
-    int32_t n_static_seats;                // fused kernel: decode seats that start with four fixed units
+    const int32_t *dq_begin;               // [kXcdQueues + 1]: decode queue q holds units dq_begin[q] .. dq_begin[q+1]-1
+    int32_t n_static_seats;                // decode seats that start with four fixed units (units 0 .. 4*seats-1)
     int32_t p_ratio, d_ratio;
     float scale_log2;                      // softmax_scale * log2(e)
 };

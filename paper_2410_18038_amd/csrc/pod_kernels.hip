@@ -146,7 +146,42 @@ __device__ __forceinline__ void write_trace(const KernelArgs &a, int slot, int c
     a.trace[slot] = r;
 }
 
+// Stores the compiler's bookkeeping of outstanding memory operations does not see.  On this
+// target loads and stores share one counter; once a store may be outstanding the compiler assumes
+// that the counter no longer falls in issue order and makes every later wait for a load a wait
+// for everything.  The decode worker keeps a ring of loads in flight while it writes a finished
+// unit's results, so it issues those few stores this way.  A wait sized for the loads alone is
+// still safe with extra stores in flight: loads complete in order among themselves, so by the
+// time all but the newest N operations have completed, the oldest load is among the completed.
+// Nothing in these kernels reads the stored data back, and a kernel's end completes its stores.
+__device__ __forceinline__ void store16_untracked(void *p, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store8_untracked(void *p, u32x2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off" ::"v"(p), "v"(v) : "memory");
+}
+
+// Append one record to the event log (one lane calls this).
+__device__ __forceinline__ void log_event(const KernelArgs &a, int kind, int item, uint64_t t_begin)
+{
+    const uint64_t t_end = wall_clock64();
+    const uint32_t k = atomicAdd(a.evlog, 1u);
+    if (k < a.evlog_cap) {
+        EventRecord *r = (EventRecord *)(a.evlog + 4) + k;
+        const uint32_t cu = __smid() & (kCuSlots - 1);
+        const uint32_t wg = blockIdx.x * kWavesPerWg + (threadIdx.x >> 6);
+        store16_untracked(r, u32x4{(uint32_t)kind, (uint32_t)item, cu, wg});
+        store16_untracked(&r->t_begin, u32x4{(uint32_t)t_begin, (uint32_t)(t_begin >> 32), (uint32_t)t_end,
+                                             (uint32_t)(t_end >> 32)});
+    }
+}
+
 __device__ __forceinline__ u32x4 load16(const void *p) { return *(const u32x4 *)p; }
+// Same, for data that is read once: marked non-temporal so that it does not push reusable
+// data (the prefill operation's K/V tiles, shared by the workgroups of a K/V head) out of L2.
+__device__ __forceinline__ u32x4 load16_stream(const void *p) { return __builtin_nontemporal_load((const u32x4 *)p); }
 
 // ------------------------------------------------------------------------------------------
 // Prefill path (Sections 2.1 and 4.3: the prefill operation as a device function that takes
@@ -563,20 +598,28 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 
 // ------------------------------------------------------------------------------------------
 // Decode path (Section 4.2.3: a decode workgroup is cut into one-wavefront virtual units, so
-// no workgroup barrier is used here).  A unit streams its K and V rows once from HBM with fully
-// coalesced 16-byte loads.  The rows of the next kRing-1 steps (16 keys each) are in flight in a
-// ring of registers, which is where the bytes-in-flight needed to cover HBM latency live: the
-// fused kernel's register budget is set by the prefill role, and the decode role spends it on
-// this ring.  A small wavefront-private LDS region only turns 16 rows at a time into MFMA
-// operands.  The query heads of the group are the (zero padded) 16 columns of the products, so
-// the matrix unit is busy for a few percent of the time only (Section 4.2.1).
+// no workgroup barrier is used here).  A wavefront is a persistent worker over a stream of decode
+// units.  It reads K and V rows once from HBM with fully coalesced 16-byte loads; the rows of the
+// next kRing-1 steps (16 keys each) are in flight in a ring of registers, which is where the
+// bytes-in-flight needed to cover HBM latency live: the fused kernel's register budget is set by
+// the prefill role, and the decode role spends it on this ring.  The ring runs on across unit
+// boundaries: the "head" (the step being requested from memory) moves into the next unit while
+// the "tail" (the step being computed) finishes the current one, so a boundary costs no drained
+// pipeline.  For that the next unit is claimed, its descriptor read and its query heads copied
+// to LDS a couple of ring turns before the head needs them.  A small wavefront-private LDS region
+// turns 16 rows at a time into MFMA operands.  The query heads of the group are the (zero
+// padded) 16 columns of the products, so the matrix unit is busy for a few percent of the time
+// only (Section 4.2.1).
 // ------------------------------------------------------------------------------------------
 template <int D> struct DecodeLds {
     static constexpr int kKStride = D * 2 + 16;
     static constexpr int kVStride = D * 2 + 32;
     static constexpr int kKBytes = kDecodeStep * kKStride;
     static constexpr int kVBytes = kDecodeStep * kVStride;
-    static constexpr int kBytesPerWave = kKBytes + kVBytes;
+    static constexpr int kQSlice = kWaveSize * 16;             // one 16-byte piece per lane
+    static constexpr int kQBuf = (D / 32) * kQSlice;           // one unit's query heads as MFMA operands
+    static constexpr int kQBytes = 2 * kQBuf;                  // the tail's unit and the unit fetched ahead
+    static constexpr int kBytesPerWave = kKBytes + kVBytes + kQBytes;
     static constexpr int kBytes = kBytesPerWave * kWavesPerWg;
 };
 
@@ -586,12 +629,29 @@ template <int D, int LAYOUT> struct DecodeRing {
     static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 4 : 5) : 8;
 };
 
+// Placed right after a branch on a per-lane condition inside code that keeps wavefront-uniform
+// state: the join of that branch stays a block of its own, so the compiler does not merge it
+// with joins of uniform branches (which would make it treat the uniform state as per-lane and
+// move it to vector registers).  Emits no instruction.
+__device__ __forceinline__ void lane_test_done() { __builtin_amdgcn_wave_barrier(); }
+
+template <int N_OPS> __device__ __forceinline__ void wait_loads_but()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_OPS) : "memory");
+}
+
+// A decode worker.  Worker number `seat` (seats are handed out once per workgroup) starts with the
+// fixed units 4*seat .. 4*seat+3, one per wavefront, when seat < n_static_seats: a chip-wide
+// burst of claims at the start of a launch would be served one at a time by the memory system.
+// After that a wavefront claims units from the queue of its XCD, then from the other queues.
+// Returns the number of units the wavefront ran.
 template <int DT, int D, int LAYOUT>
-__device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int unit_index,
-                                                unsigned char *smem_wave)
+__device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned char *smem, const int seat,
+                                                 const int xcd)
 {
     using N = Num<DT>;
     using v8 = typename N::v8;
+    using elem = typename N::elem;
     using L = DecodeLds<D>;
     constexpr int KS = D / 32;                     // 32-channel slices of the QK^T contraction
     constexpr int MB = D / 16;                     // 16-channel blocks of the output
@@ -599,66 +659,129 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
     constexpr int RPI = kWaveSize / CH;            // rows per load instruction
     constexpr int NLD = kDecodeStep / RPI;         // load instructions per step, for K and for V
     constexpr int R = DecodeRing<D, LAYOUT>::kDepth;
+    constexpr int kDummy = 0x3fffffff;             // slot holds no step (all its keys are masked)
+    constexpr int kClaimAhead = 2 * R;             // the head claims its next unit this many steps before it runs out
 
-    // The unit descriptor and everything derived from it is wavefront-uniform: read it through
-    // the constant address space so that it lives in scalar registers.
-    DecodeUnit u;
-    {
-        const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.dunits + 8 * (int64_t)unit_index;
-        u.req = w[0]; u.kv_head = w[1]; u.t0 = w[2]; u.t1 = w[3]; u.prow0 = w[4]; u.split = w[5];
-        u.pad0 = 0; u.pad1 = 0;
-    }
-    const POD_CONST int32_t *meta = (const POD_CONST int32_t *)a.seq_meta + 4 * u.req;
-    const int q_start = meta[0], cache_row = meta[3];
-
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
     const int n16 = lane & 15;                     // query column (head within the group)
     const int b4 = lane >> 4;
     const int group = a.group;
     const int token_elems = a.n_kv_heads * D;
     const bool col_ok = n16 < group;
-    const int hq = u.kv_head * group + n16;
-
-    v8 q[KS];
-    {
-        const typename N::elem *qp = (const typename N::elem *)a.decode_q +
-            ((int64_t)q_start * a.n_q_heads + hq) * D + b4 * 8;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (col_ok) raw = load16(qp + ks * 32);
-            q[ks] = __builtin_bit_cast(v8, raw);
-        }
-    }
-
-    f32x4 o[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = neg_inf(), l_run = 0.f;
     const float c = a.scale_log2;
-
-    const typename N::elem *kc = (const typename N::elem *)a.k_cache + u.kv_head * D;
-    const typename N::elem *vc = (const typename N::elem *)a.v_cache + u.kv_head * D;
-    POD_LDS unsigned char *const lds_k = (POD_LDS unsigned char *)smem_wave;
-    POD_LDS unsigned char *const lds_v = lds_k + L::kKBytes;
     const int ld_row = lane / CH, ld_chunk = lane % CH;
+    POD_LDS unsigned char *const lds_k = (POD_LDS unsigned char *)(smem + wave * L::kBytesPerWave);
+    POD_LDS unsigned char *const lds_v = lds_k + L::kKBytes;
+    POD_LDS unsigned char *const lds_q = lds_v + L::kVBytes;
+    const POD_CONST int32_t *const dq = (const POD_CONST int32_t *)a.dq_begin;
 
-    const int n_steps = (u.t1 - u.t0 + kDecodeStep - 1) / kDecodeStep;
-    const POD_CONST int32_t *table = (const POD_CONST int32_t *)a.block_table +
-                                     (int64_t)cache_row * a.max_blocks_per_seq;
+    // Unit descriptors and everything derived from them are wavefront-uniform: they are read
+    // through the constant address space so that they live in scalar registers.
+    struct Desc { int id, kv_head, t0, t1, prow0, q_start, cache_row; };
+    auto load_desc = [&](int idx) __attribute__((always_inline)) -> Desc {
+        idx = __builtin_amdgcn_readfirstlane(idx);
+        const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.dunits + 8 * (int64_t)idx;
+        Desc d;
+        d.id = idx;
+        d.kv_head = w[1]; d.t0 = w[2]; d.t1 = w[3]; d.prow0 = w[4]; d.q_start = w[6]; d.cache_row = w[7];
+        return d;
+    };
 
-    // All loads are unconditional so that the compiler's wait counters stay exact (a branch around
-    // a load makes it drain the whole ring): steps past the end re-read the last step and rows
-    // past the end re-read the last row; such keys are masked out of the softmax by their index.
-    const int t_last_step = u.t0 + (n_steps - 1) * kDecodeStep;
+    // ---- claims ------------------------------------------------------------------------
+    // The compiler keeps exact counts of the loads in flight only as long as every path through
+    // the ring's loop issues the same memory operations.  So a claim that must be waited for on
+    // the spot is one opaque instruction pair (the atomic and its wait), and the claim issued
+    // ahead of its use is part of every turn of the ring: a turn that wants no unit adds zero to
+    // a word of its own workgroup instead.
+    int cq = __builtin_amdgcn_readfirstlane(xcd) & (kXcdQueues - 1), tried = 0;
+    auto claim_now = [&]() __attribute__((always_inline)) -> int {
+        uint32_t v = 0;
+        if (lane == 0) {
+            uint32_t *ctr = &a.hdr->next_dunit_xcd[cq][0];
+            asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)"
+                         : "=&v"(v) : "v"(ctr), "v"(1u) : "memory");
+        }
+        lane_test_done();
+        return (int)__builtin_amdgcn_readfirstlane(v);
+    };
+    // Turns a claimed counter value into a unit index.  When the queue is used up it claims from
+    // the next queues (and waits for those claims); -1 when no unit is left anywhere.
+    auto claim_resolve = [&](int k) __attribute__((always_inline)) -> int {
+        for (;;) {
+            const int q0 = dq[cq], q1 = dq[cq + 1];
+            if (k < q1 - q0) return q0 + k;
+            do {
+                cq = (cq + 1) & (kXcdQueues - 1);
+                ++tried;
+            } while (tried < kXcdQueues && dq[cq + 1] == dq[cq]);
+            if (tried >= kXcdQueues) return -1;
+            k = claim_now();
+        }
+    };
 
-    // Element offset of the first row of step `st` (LAYOUT 0 and 1: uniform; LAYOUT 2 handles rows itself).
-    auto step_base = [&](int st) -> int64_t {
-        const int t = min(u.t0 + st * kDecodeStep, t_last_step);
+    // ---- the next unit's query heads: global memory -> LDS, asynchronously ----------------
+    // The query heads of the next unit are copied to LDS ahead of time (two buffers, used in
+    // turn) and moved to registers when the tail enters the unit.  Lanes of columns beyond the
+    // group read zeros written once.
+    int q_cur = 0;                                 // buffer of the tail's unit
+    if (!col_ok) {
+#pragma unroll
+        for (int i = 0; i < 2 * KS; ++i) *(POD_LDS u32x4 *)(lds_q + i * L::kQSlice + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+    }
+    lane_test_done();
+    auto q_dma = [&](const Desc &d, int buf) __attribute__((always_inline)) {
+        const char *qb = (const char *)((const elem *)a.decode_q +
+                                        ((int64_t)d.q_start * a.n_q_heads + d.kv_head * group) * D);
+        const uint32_t vo = (uint32_t)(n16 * D + b4 * 8) * 2u;
+        const uint32_t dst = (uint32_t)(uintptr_t)lds_q + (uint32_t)(buf * L::kQBuf);
+        if (col_ok) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) dma16_vaddr(dst + ks * L::kQSlice, qb + vo + ks * 64);
+        }
+        lane_test_done();
+    };
+    v8 q[KS];
+    auto q_from_lds = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            q[ks] = *(const POD_LDS v8 *)(lds_q + q_cur * L::kQBuf + ks * L::kQSlice + lane * 16);
+    };
+
+    // ---- head: the step whose rows are requested next ----------------------------------------
+    Desc hu, cu, nx;                               // units of the head, of the tail, and the one fetched ahead
+    int h_t = 0;                                   // first key of the head's next step; >= hu.t1: the head has run out
+    int h_addr_t = 0;                              // first key of the step the addresses below point at
+    int64_t h_base = 0;                            // element offset (head 0, channel 0) of that step
+    uint32_t voff[NLD];                            // per-lane byte offsets inside that step
+    const elem *kc = nullptr, *vc = nullptr;
+    const POD_CONST int32_t *table = nullptr;
+    // State bits (one word: separate flags end up addressed through a common pointer and then
+    // live in scratch memory).
+    constexpr uint32_t kHeadInTail = 1u;           // head and tail are in the same unit
+    constexpr uint32_t kNextValid = 2u;            // `nx` holds a fetched unit, its query heads are in (or on their way to) LDS
+    constexpr uint32_t kClaimPending = 4u;         // a claim has been issued and not looked at yet
+    constexpr uint32_t kExhausted = 8u;            // every queue has been found empty
+    constexpr uint32_t kDone = 16u;                // the tail has finished the last unit
+    uint32_t st = kHeadInTail;
+    uint32_t claim_v = 0;                          // lane 0: counter value returned by the claim of the current turn
+    int n_iss = 0, q_mark = 0;                     // steps issued so far; their count when the last Q copy was issued
+
+    // Rows past the end of a unit's last step re-read its last row (the keys are masked out of the
+    // softmax by index), so every load is in bounds and none sits behind a branch.
+    auto set_voff = [&](int t_first, int t1) __attribute__((always_inline)) {
+        const int last_row = min(t1 - 1 - t_first, kDecodeStep - 1);
+#pragma unroll
+        for (int p = 0; p < NLD; ++p) {
+            const int row = min(p * RPI + ld_row, last_row);
+            voff[p] = (uint32_t)(row * token_elems + ld_chunk * 8) * 2u;
+        }
+    };
+    auto base_of = [&](int cache_row, int t) __attribute__((always_inline)) -> int64_t {
         if constexpr (LAYOUT == kLayoutContiguous) {
             return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
         } else if constexpr (LAYOUT == kLayoutPaged16) {
-            // block_size is a power of two >= 16 and t0 a multiple of 16: a step never straddles blocks
+            // block_size is a power of two >= 16 and t a multiple of 16: a step never straddles blocks
             const int bi = t >> a.bs_shift, off = t & (a.block_size - 1);
             const int blk = table[bi];
             return ((int64_t)blk * a.block_size + off) * token_elems;
@@ -666,47 +789,75 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
             return 0;
         }
     };
-
-    // Per-lane byte offsets inside a step, computed once: the step's base address is uniform and
-    // stays in scalar registers, so issuing a step costs no vector arithmetic.  The last step of
-    // the unit uses offsets clamped to its last existing row.
-    uint32_t voff_full[NLD], voff_tail[NLD];
-    {
-        const int last_row = u.t1 - 1 - t_last_step;          // 0..15
-#pragma unroll
-        for (int p = 0; p < NLD; ++p) {
-            const int row = p * RPI + ld_row;
-            voff_full[p] = (uint32_t)(row * token_elems + ld_chunk * 8) * 2u;
-            voff_tail[p] = (uint32_t)(min(row, last_row) * token_elems + ld_chunk * 8) * 2u;
-        }
-    }
+    auto set_head = [&](const Desc &d) __attribute__((always_inline)) {
+        hu = d;
+        h_t = d.t0;
+        h_addr_t = d.t0;
+        kc = (const elem *)a.k_cache + d.kv_head * D;
+        vc = (const elem *)a.v_cache + d.kv_head * D;
+        table = (const POD_CONST int32_t *)a.block_table + (int64_t)d.cache_row * a.max_blocks_per_seq;
+        h_base = base_of(d.cache_row, d.t0);
+        set_voff(d.t0, d.t1);
+    };
 
     struct Slot { u32x4 k[NLD], v[NLD]; };
-    auto issue = [&](Slot &sl, int st, int64_t base) {
+    // Request the head's step into a slot.  When the head has run out, the last step is read again
+    // and the slot is marked as holding nothing.
+    auto issue_step = [&](Slot &sl, int &slot_t) __attribute__((always_inline)) {
+        slot_t = h_t < hu.t1 ? h_t : kDummy;
         if constexpr (LAYOUT == kLayoutPagedAny) {
-            const int t_first = min(u.t0 + st * kDecodeStep, t_last_step);
-            const int last_row = u.t1 - 1 - t_first;         // >= 0
+            const int last_row = hu.t1 - 1 - h_addr_t;       // >= 0
 #pragma unroll
             for (int p = 0; p < NLD; ++p) {
                 const int row = min(p * RPI + ld_row, last_row);
-                const int64_t off = token_offset<true>(a, cache_row, t_first + row, token_elems) + ld_chunk * 8;
-                sl.k[p] = load16(kc + off);
-                sl.v[p] = load16(vc + off);
+                const int64_t off = token_offset<true>(a, hu.cache_row, h_addr_t + row, token_elems) + ld_chunk * 8;
+                sl.k[p] = load16_stream(kc + off);
+                sl.v[p] = load16_stream(vc + off);
             }
         } else {
-            const bool tail = st >= n_steps - 1;              // uniform
-            const char *kb = (const char *)(kc + base);
-            const char *vb = (const char *)(vc + base);
+            const char *kb = (const char *)(kc + h_base);
+            const char *vb = (const char *)(vc + h_base);
 #pragma unroll
             for (int p = 0; p < NLD; ++p) {
-                const uint32_t vo = tail ? voff_tail[p] : voff_full[p];
-                sl.k[p] = load16(kb + vo);
-                sl.v[p] = load16(vb + vo);
+                sl.k[p] = load16_stream(kb + voff[p]);
+                sl.v[p] = load16_stream(vb + voff[p]);
+            }
+        }
+        ++n_iss;
+    };
+    auto advance_head = [&]() __attribute__((always_inline)) {
+        if (h_t < hu.t1) {
+            h_t += kDecodeStep;
+            if (h_t < hu.t1) {
+                h_addr_t = h_t;
+                if constexpr (LAYOUT == kLayoutContiguous) h_base += (int64_t)kDecodeStep * token_elems;
+                else h_base = base_of(hu.cache_row, h_t);
+                if (h_t + kDecodeStep > hu.t1) set_voff(h_t, hu.t1);     // ragged last step
             }
         }
     };
-    auto consume = [&](const Slot &sl, int st) {
-        const int t_first = u.t0 + st * kDecodeStep;
+    // Claim result -> descriptor -> query copy.  Waits for the claim and for the descriptor.
+    auto fetch_next = [&]() __attribute__((always_inline)) {
+        int idx = -1;
+        if (st & kClaimPending) idx = claim_resolve((int)__builtin_amdgcn_readfirstlane(claim_v));
+        else if (!(st & kExhausted)) idx = claim_resolve(claim_now());
+        st &= ~kClaimPending;
+        nx = load_desc(max(idx, 0));
+        q_mark = idx >= 0 ? n_iss : q_mark;
+        st |= idx >= 0 ? kNextValid : kExhausted;
+        if (idx >= 0) q_dma(nx, q_cur ^ 1);
+    };
+
+    // ---- tail: the step being computed ------------------------------------------------------------
+    f32x4 o[MB];
+    float m_run, l_run;
+    auto reset_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = neg_inf();
+        l_run = 0.f;
+    };
+    auto consume = [&](const Slot &sl, const int t_first) __attribute__((always_inline)) {
 #pragma unroll
         for (int p = 0; p < NLD; ++p) {
             const int row = p * RPI + ld_row;
@@ -721,7 +872,7 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
             const v8 kk = *(const POD_LDS v8 *)(lds_k + n16 * L::kKStride + (ks * 32 + b4 * 8) * 2);
             s = N::mfma16(kk, q[ks], s);
         }
-        const int n_valid = u.t1 - t_first - 4 * b4;          // keys of this lane that exist
+        const int n_valid = cu.t1 - t_first - 4 * b4;         // keys of this lane that exist
 #pragma unroll
         for (int r = 0; r < 4; ++r) s[r] = (r < n_valid) ? s[r] : neg_inf();
         float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
@@ -740,7 +891,7 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         for (int r = 0; r < 4; ++r) {
             const float p = fast_exp2(__builtin_fmaf(s[r], c, -m_use));
             l_run += p;
-            pk[r] = (typename N::elem)p;
+            pk[r] = (elem)p;
         }
         // O^T += V^T P^T over these 16 keys: lane's contraction slots 4*b4 + r are keys 4*b4 + r.
 #pragma unroll
@@ -751,57 +902,125 @@ __device__ __forceinline__ void decode_unit_run(const KernelArgs &a, const int u
         }
         wave_lds_sync();                           // all reads issued before the next step overwrites
     };
+    // o[mb][r] is channel mb*16 + 4*b4 + r of query column n16.
+    auto finish_unit = [&](const Desc &d) __attribute__((always_inline)) {
+        const float l_tot = sum_across_32(sum_across_16(l_run));
+        if (col_ok) {
+        if (d.prow0 < 0) {
+            const float inv = 1.f / l_tot;
+            elem *op = (elem *)a.out +
+                ((int64_t)(a.n_prefill_rows + d.q_start) * a.n_q_heads + d.kv_head * group + n16) * D;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                typename N::v4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (elem)(o[mb][e] * inv);
+                store8_untracked(op + mb * 16 + 4 * b4, __builtin_bit_cast(u32x2, w));
+            }
+        } else {
+            const int64_t prow = (int64_t)d.prow0 + n16;
+            float *po = a.part_o + prow * D;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) store16_untracked(po + mb * 16 + 4 * b4, __builtin_bit_cast(u32x4, o[mb]));
+            if (b4 == 0)
+                store8_untracked(a.part_ml + prow * 2, u32x2{__float_as_uint(m_run), __float_as_uint(l_tot)});
+        }
+        }
+        lane_test_done();
+    };
 
-    // Ring of R slots: while step st is consumed, steps st+1 .. st+R-1 are in flight.
+    // ---- first unit -------------------------------------------------------------------------------
+    int n_done = 0;
+    {
+        int idx0;
+        if (seat < a.n_static_seats) idx0 = __builtin_amdgcn_readfirstlane(seat) * kWavesPerWg + wave;
+        else idx0 = claim_resolve(claim_now());
+        if (idx0 < 0) return 0;
+        set_head(load_desc(idx0));
+        cu = hu;
+        q_dma(cu, 0);
+    }
+    uint64_t tb = a.evlog ? wall_clock64() : 0;
+    reset_acc();
+
     Slot ring[R];
-    int64_t next_base = step_base(0);
+    int slot_t[R];
+    uint32_t *const null_ctr = &a.hdr->null_claim[blockIdx.x & (kNullClaimLines - 1)][wave];
 #pragma unroll
     for (int r = 0; r < R - 1; ++r) {
-        issue(ring[r], r, next_base);
+        issue_step(ring[r], slot_t[r]);
         __builtin_amdgcn_sched_barrier(0);         // loads return in issue order: keep oldest first
-        next_base = step_base(r + 1);
+        advance_head();
     }
-    // The body of a full turn of the ring is branch-free (a branch around a load would make the
-    // compiler's load counters drain the ring): a turn that runs past the last step consumes
-    // re-read rows whose keys are all masked by index, which changes nothing.
-#pragma unroll 1
-    for (int base = 0; base < n_steps; base += R) {
+    // The query copy is older than every ring load (the any-block-size layout issues more loads
+    // than counted here and only waits longer).
+    wait_loads_but<(R - 1) * 2 * NLD>();
+    q_from_lds();
+
+    // A full turn of the ring.  The rarely taken blocks below hold no K/V load, so the compiler's
+    // load counters stay exact on the common path and a step waits only for its own slot.
+    while (!(st & kDone)) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int st = base + r;
-            issue(ring[(r + R - 1) % R], st + R - 1, next_base);
+            if (r == 0) {
+                // Claim ahead, once the head is close to the end of its unit: the answer is picked
+                // up at the end of this turn, by when the slot requested right after the claim
+                // has been waited for, and memory operations return in issue order.
+                const bool want = st == kHeadInTail && hu.t1 - h_t <= kClaimAhead * kDecodeStep;
+                st |= want ? kClaimPending : 0u;
+                uint32_t *ctr = want ? &a.hdr->next_dunit_xcd[cq][0] : null_ctr;
+                if (lane == 0) claim_v = atomicAdd(ctr, want ? 1u : 0u);
+                lane_test_done();
+            }
+            // The head moves on once it has run out of its unit, the next unit is known and the
+            // tail has reached the head's unit (the ring holds at most one unit boundary).
+            if (h_t >= hu.t1 && (st & (kNextValid | kHeadInTail)) == (kNextValid | kHeadInTail)) {
+                set_head(nx);
+                st &= ~(kNextValid | kHeadInTail);
+            }
+            issue_step(ring[(r + R - 1) % R], slot_t[(r + R - 1) % R]);
             __builtin_amdgcn_sched_barrier(0);     // the new loads go out before this step's work
-            next_base = step_base(st + R);
-            consume(ring[r], st);
+            advance_head();
+            const int t_first = slot_t[r];
+            consume(ring[r], t_first);
             __builtin_amdgcn_sched_barrier(0);
+            if (t_first != kDummy && t_first + kDecodeStep >= cu.t1) {
+                // last step of the tail's unit
+                finish_unit(cu);
+                if (a.evlog) {
+                    if (lane == 0) log_event(a, kDecode, cu.id, tb);
+                    lane_test_done();
+                }
+                ++n_done;
+                if (st & kHeadInTail) {
+                    // the head has run out of this unit and has nowhere to go yet
+                    if (!(st & kNextValid)) fetch_next();
+                    // Nothing left: the turn is finished with empty slots (leaving the loop from
+                    // inside a turn makes the compiler lose its exact load counts), then the
+                    // worker returns.
+                    if (st & kNextValid) set_head(nx);
+                    else st |= kDone;
+                    st &= ~kNextValid;
+                }
+                cu = hu;
+                st |= kHeadInTail;
+                if (n_iss - q_mark < R) wait_all_loads();    // the query copy may still be in flight
+                q_cur ^= 1;
+                q_from_lds();
+                reset_acc();
+                if (a.evlog) tb = wall_clock64();
+            }
+            if (r == R - 1) {
+                // (the claim's answer is read in every turn, wanted or not, so that every path
+                // through a turn has the same outstanding operations)
+                claim_v = (uint32_t)__builtin_amdgcn_readfirstlane(claim_v);
+                if (st & kClaimPending) fetch_next();
+            }
         }
     }
-
-    // o[mb][r] is channel mb*16 + 4*b4 + r of query column n16.
-    const float l_tot = sum_across_32(sum_across_16(l_run));
-    if (!col_ok) return;
-    if (u.prow0 < 0) {
-        const float inv = 1.f / l_tot;
-        typename N::elem *op = (typename N::elem *)a.out +
-            ((int64_t)(a.n_prefill_rows + q_start) * a.n_q_heads + hq) * D;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-            typename N::v4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (typename N::elem)(o[mb][e] * inv);
-            *(typename N::v4 *)(op + mb * 16 + 4 * b4) = w;
-        }
-    } else {
-        const int64_t prow = (int64_t)u.prow0 + n16;
-        float *po = a.part_o + prow * D;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) *(f32x4 *)(po + mb * 16 + 4 * b4) = o[mb];
-        if (b4 == 0) {
-            a.part_ml[prow * 2 + 0] = m_run;
-            a.part_ml[prow * 2 + 1] = l_tot;
-        }
-    }
+    return n_done;
 }
+
 
 template <int D> struct FusedLds {
     static constexpr int kBytes = PrefillLds<D>::kBytes > DecodeLds<D>::kBytes ? PrefillLds<D>::kBytes
@@ -819,40 +1038,6 @@ __global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
     prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
     if (a.trace && threadIdx.x == 0)
         write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
-}
-
-// A decode worker: each wavefront runs decode units until none is left (the workgroup's four
-// wavefronts are independent "virtual" units, Section 4.2.3).  Claims on one shared counter are
-// served one at a time by the memory system, and a chip-wide burst of them at the start of a
-// launch costs tens of microseconds.  So worker number `seat` (seats are handed out once per
-// workgroup) first takes the four units 4*seat .. 4*seat+3 without any counter when
-// seat < n_static_seats, and only then claims from the counter, which hands out the units from
-// 4*n_static_seats on.  (Issuing a claim early, before the previous unit's work, was tried and
-// is slower: loads return in order, so everything issued after a slow claim waits for it.)
-template <int DT, int D, int LAYOUT>
-__device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned char *smem, int seat,
-                                                 int n_static_seats)
-{
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    unsigned char *smem_wave = smem + wave * DecodeLds<D>::kBytesPerWave;
-    int n_done = 0;
-    if (seat < n_static_seats) {
-        const int unit = seat * kWavesPerWg + wave;
-        if (unit < a.n_dunits) {
-            decode_unit_run<DT, D, LAYOUT>(a, unit, smem_wave);
-            ++n_done;
-        }
-    }
-    const uint32_t first_dynamic = (uint32_t)(n_static_seats * kWavesPerWg);
-    for (;;) {
-        uint32_t unit = 0;
-        if ((threadIdx.x & 63) == 0) unit = atomicAdd(&a.hdr->next_unit, 1u);
-        unit = __builtin_amdgcn_readfirstlane(unit) + first_dynamic;
-        if (unit >= (uint32_t)a.n_dunits) break;
-        decode_unit_run<DT, D, LAYOUT>(a, (int)unit, smem_wave);
-        ++n_done;
-    }
-    return n_done;                                  // units done by this wavefront
 }
 
 // A prefill worker: the workgroup claims prefill items until none is left, first from the queue
@@ -882,7 +1067,9 @@ __device__ __forceinline__ int prefill_worker_run(const KernelArgs &a, unsigned 
         q = slot[1] & 255;
         tried = slot[1] >> 8;
         if (item < 0) break;
+        const uint64_t tb = a.evlog ? wall_clock64() : 0;
         prefill_item_run<DT, D, LAYOUT>(a, a.pitems[item], smem);
+        if (a.evlog && threadIdx.x == 0) log_event(a, kPrefill, item, tb);
         ++n_done;
     }
     return n_done;
@@ -903,7 +1090,7 @@ __device__ __forceinline__ void finish_and_reset(WsHeader *hdr, int *flag)
         if (threadIdx.x == 0) {
             hdr->next_item[0] = 0u;
             hdr->next_item[1] = 0u;
-            hdr->next_unit = 0u;
+            for (int q = 0; q < kXcdQueues; ++q) hdr->next_dunit_xcd[q][0] = 0u;
             hdr->done = 0u;
             for (int q = 0; q < kXcdQueues; ++q) hdr->next_pitem_xcd[q] = 0u;
         }
@@ -917,7 +1104,8 @@ __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
     __shared__ int flag;
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
     // every workgroup of this kernel is a decode worker; its seat is its index
-    const int n_done = decode_worker_run<DT, D, LAYOUT>(a, smem, blockIdx.x, gridDim.x);
+    const int xcd = __builtin_amdgcn_readfirstlane((int)(__smid() >> 6));
+    const int n_done = decode_worker_run<DT, D, LAYOUT>(a, smem, blockIdx.x, xcd);
     if (a.trace) {
         __syncthreads();
         if (threadIdx.x == 0)
@@ -969,10 +1157,10 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
         n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
         if (a.trace) t_switch = wall_clock64();
         const int seat = take_seat();
-        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
+        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd);
     } else {
         const int seat = take_seat();
-        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, a.n_static_seats);
+        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd);
         if (a.trace) t_switch = wall_clock64();
         n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
     }

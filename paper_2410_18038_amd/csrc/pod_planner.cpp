@@ -192,9 +192,11 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         for (int r = prm.n_prefill; r < n_req; ++r) token_heads += (int64_t)seq_meta[4 * r + 2] * prm.n_kv_heads;
         int chunk = prm.decode_chunk;
         if (chunk <= 0) {
-            // About two units per resident wavefront slot: ragged contexts still balance (units are
-            // claimed longest first), and units stay long enough (>= 512 keys) that their start-up
-            // (descriptor, Q, first K/V rows) and their partial rows stay small next to the stream.
+            // About two units per resident wavefront slot: ragged contexts and wavefronts of
+            // unequal speed still balance (units are claimed longest first), and units stay long
+            // enough (>= 512 keys) that their partial rows stay small next to the stream.
+            // (Measured: finer cuts gain nothing once the ring runs on across unit boundaries,
+            // and cost partial rows and claims.)
             const int64_t slots = (int64_t)n_cus * 8;
             chunk = (int)std::min<int64_t>(2048, std::max<int64_t>(512, (token_heads + 2 * slots - 1) / (2 * slots)));
             chunk = round_up(chunk, 256);
@@ -220,7 +222,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
                     u.t0 = i * tps;
                     u.t1 = std::min(kv_len, (i + 1) * tps);
                     u.prow0 = s_eff > 1 ? (int32_t)(prow_base + (int64_t)i * group) : -1;
-                    u.split = i; u.pad0 = 0; u.pad1 = 0;
+                    u.split = i; u.q_start = seq_meta[4 * r]; u.cache_row = seq_meta[4 * r + 3];
                     plan.dunits.push_back(u);
                 }
                 plan.max_dsplits = std::max(plan.max_dsplits, s_eff);
@@ -232,6 +234,22 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         // Decode workers are persistent: each of their wavefronts claims units until none is left.
         // Two workgroups fit on a compute unit, so more workers than that would only queue.
         plan.n_dwgs = std::min(2 * n_cus, ceil_div((int)plan.dunits.size(), kWavesPerWg));
+        // The first workers to take a decode seat (one per compute unit) start with four fixed
+        // units each, the longest ones, and claim nothing for them.  The other units are dealt
+        // round-robin, still longest first, to one queue per XCD: a wavefront claims from the
+        // queue of the XCD it runs on and moves to the next queue when that one is empty, so the
+        // eight counters are each hit by an eighth of the chip.
+        const int n_units = (int)plan.dunits.size();
+        plan.n_static_seats = std::min(n_cus, n_units / kWavesPerWg);
+        const int n_fixed = plan.n_static_seats * kWavesPerWg;
+        std::vector<DecodeUnit> dealt;
+        dealt.reserve((size_t)(n_units - n_fixed));
+        for (int q = 0; q < kXcdQueues; ++q) {
+            plan.dq_begin[q] = n_fixed + (int)dealt.size();
+            for (int j = n_fixed + q; j < n_units; j += kXcdQueues) dealt.push_back(plan.dunits[(size_t)j]);
+        }
+        plan.dq_begin[kXcdQueues] = n_units;
+        std::copy(dealt.begin(), dealt.end(), plan.dunits.begin() + n_fixed);
     }
     if (next_prow > (int64_t)1 << 30) { err = "too many partial rows"; return POD_ERR_INVALID_ARG; }
     plan.n_partial_rows = next_prow;
@@ -258,6 +276,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     plan.off_dunits = off;   off = align256(off + plan.dunits.size() * sizeof(DecodeUnit));
     plan.off_centries = off; off = align256(off + plan.centries.size() * sizeof(CombineEntry));
     plan.off_crows = off;    off = align256(off + plan.crows.size() * sizeof(int32_t));
+    plan.off_dq = off;       off = align256(off + sizeof plan.dq_begin);
     plan.off_part_o = off;   off = align256(off + (size_t)plan.n_partial_rows * prm.head_dim * sizeof(float));
     plan.off_part_ml = off;  off = align256(off + (size_t)plan.n_partial_rows * 2 * sizeof(float));
     plan.ws_bytes = off;

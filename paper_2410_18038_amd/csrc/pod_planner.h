@@ -28,16 +28,20 @@ struct Plan {
     int decode_chunk = 0;
     int max_psplits = 1, max_dsplits = 1;
     int pq_begin[kXcdQueues + 1] = {0};     // per-XCD prefill queues inside pitems
+    int dq_begin[16] = {0};                 // per-XCD decode queues inside dunits (entries 0..8 used)
+    int n_static_seats = 0;                 // decode seats whose first four units are fixed
     int n_dwgs = 0;                         // workgroups of the stand-alone decode kernel
     int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)
-    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_part_o = 0, off_part_ml = 0;
+    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_dq = 0, off_part_o = 0, off_part_ml = 0;
     size_t ws_bytes = 0;
     // side streams and events of the two-stream mode, created on first use
     void *side_stream[2] = {nullptr, nullptr};
     void *events[3] = {nullptr, nullptr, nullptr};
     void *trace = nullptr;                  // device buffer for TraceRecords, or null
     size_t trace_bytes = 0;
+    void *evlog = nullptr;                  // device buffer for the event log, or null
+    size_t evlog_bytes = 0;
 };
 
 // Validates and fills `plan`; returns POD_OK or an error code with a message in `err`.

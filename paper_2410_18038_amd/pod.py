@@ -24,8 +24,10 @@ MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
 
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
-           "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_upload", "pod_attn_forward",
+           "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_set_event_log",
+           "pod_attn_plan_upload", "pod_attn_forward",
            "pod_attn_simulate_binder", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
+           "pod_attn_plan_decode_queue",
            "pod_attn_probe_hbm_read", "pod_attn_probe_mfma",
            "pod_attn_last_error", "pod_attn_version"]
 
@@ -85,6 +87,8 @@ def lib():
         L.pod_attn_plan_info_get.argtypes = [vp, ctypes.POINTER(PlanInfo)]
         L.pod_attn_plan_set_trace.restype = ctypes.c_int
         L.pod_attn_plan_set_trace.argtypes = [vp, vp, ctypes.c_size_t]
+        L.pod_attn_plan_set_event_log.restype = ctypes.c_int
+        L.pod_attn_plan_set_event_log.argtypes = [vp, vp, ctypes.c_size_t]
         L.pod_attn_workspace_size.restype = ctypes.c_size_t
         L.pod_attn_workspace_size.argtypes = [vp]
         L.pod_attn_plan_upload.restype = ctypes.c_int
@@ -99,6 +103,9 @@ def lib():
         L.pod_attn_plan_prefill_item.argtypes = [vp, ctypes.c_int32, i32p]
         L.pod_attn_plan_decode_unit.restype = ctypes.c_int
         L.pod_attn_plan_decode_unit.argtypes = [vp, ctypes.c_int32, i32p]
+        L.pod_attn_plan_decode_queue.restype = ctypes.c_int
+        L.pod_attn_plan_decode_queue.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32),
+                                                 ctypes.POINTER(ctypes.c_int32)]
         L.pod_attn_probe_hbm_read.restype = ctypes.c_int
         L.pod_attn_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.pod_attn_probe_mfma.restype = ctypes.c_int
@@ -156,6 +163,10 @@ class Plan:
         n = self.info().n_decode_units
         return np.array([pod_attn_plan_decode_unit(self, i) for i in range(n)], dtype=np.int32).reshape(n, 8)
 
+    def decode_queues(self) -> list:
+        """[(begin, end)] of the 8 per-XCD decode queues; units before the first begin are fixed."""
+        return [pod_attn_plan_decode_queue(self, q) for q in range(8)]
+
 
 def make_params(*, n_prefill, n_decode, n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale,
                 block_size=0, max_blocks_per_seq=0, n_cache_rows=1, n_blocks=0, kv_seq_stride=0,
@@ -187,6 +198,12 @@ def pod_attn_plan_set_trace(plan: Plan, trace_ptr: int, trace_bytes: int):
     _check(lib().pod_attn_plan_set_trace(plan.handle, ctypes.c_void_p(trace_ptr), trace_bytes))
 
 
+def pod_attn_plan_set_event_log(plan: Plan, log_ptr: int, log_bytes: int):
+    _check(lib().pod_attn_plan_set_event_log(plan.handle, ctypes.c_void_p(log_ptr), log_bytes))
+
+
+EVENT_DTYPE = np.dtype([("kind", np.int32), ("item", np.int32), ("cu", np.int32), ("wg", np.int32),
+                        ("t_begin", np.uint64), ("t_end", np.uint64)])
 TRACE_DTYPE = np.dtype([("cu", np.int32), ("first_role", np.int32), ("n_first", np.int32), ("n_second", np.int32),
                         ("t_begin", np.uint64), ("t_switch", np.uint64), ("t_end", np.uint64), ("pad", np.uint64)])
 
@@ -205,6 +222,12 @@ def pod_attn_plan_decode_unit(plan: Plan, index: int):
     out = (ctypes.c_int32 * 8)()
     _check(lib().pod_attn_plan_decode_unit(plan.handle, index, out))
     return list(out)
+
+
+def pod_attn_plan_decode_queue(plan: Plan, q: int):
+    b, e = ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().pod_attn_plan_decode_queue(plan.handle, q, ctypes.byref(b), ctypes.byref(e)))
+    return int(b.value), int(e.value)
 
 
 def pod_attn_plan_upload(plan: Plan, workspace_ptr: int, workspace_bytes: int, stream: int = 0):
@@ -307,6 +330,24 @@ class HybridAttention:
 
     def disable_trace(self):
         pod_attn_plan_set_trace(self.plan, 0, 0)
+
+    def enable_event_log(self):
+        """Allocate an event log (one record per prefill item and decode unit) and switch it on."""
+        n = self.info.n_prefill_items + self.info.n_decode_units + 1
+        self.evlog = self.torch.zeros(16 + n * 32, dtype=self.torch.uint8, device=self.workspace.device)
+        pod_attn_plan_set_event_log(self.plan, self.evlog.data_ptr(), self.evlog.numel())
+
+    def read_event_log(self) -> np.ndarray:
+        """Records of the forward call made since the log was last read; clears the log."""
+        self.torch.cuda.synchronize()
+        raw = self.evlog.cpu().numpy()
+        n = min(int(raw[:4].view(np.uint32)[0]), (raw.size - 16) // 32)
+        ev = raw[16:16 + n * 32].view(EVENT_DTYPE).copy()
+        self.evlog[:16].zero_()
+        return ev
+
+    def disable_event_log(self):
+        pod_attn_plan_set_event_log(self.plan, 0, 0)
 
     def close(self):
         self.plan.close()

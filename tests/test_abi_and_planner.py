@@ -180,8 +180,27 @@ def coverage_check(prm, meta):
     for q in set(queues):
         lens = [int(i[5] - i[4]) for i, qq in zip(items, queues) if qq == q]
         assert lens == sorted(lens, reverse=True)
-    lens = [u[3] - u[2] for u in units]
-    assert lens == sorted(lens, reverse=True)
+    # decode units: fixed first units (four per seat, at most one seat per compute unit), then 8
+    # queues that tile the rest; longest first inside each range, and no fixed unit is shorter
+    # than a queued one
+    lens = [int(u[3] - u[2]) for u in units]
+    queues_d = plan.decode_queues()
+    n_fixed = queues_d[0][0]
+    assert n_fixed == 4 * min(info.n_compute_units, len(units) // 4)
+    assert lens[:n_fixed] == sorted(lens[:n_fixed], reverse=True)
+    at = n_fixed
+    for b, e in queues_d:
+        assert b == at and e >= b
+        assert lens[b:e] == sorted(lens[b:e], reverse=True)
+        at = e
+    assert at == len(units)
+    if n_fixed and n_fixed < len(units):
+        assert min(lens[:n_fixed]) >= max(lens[n_fixed:])
+    sizes = [e - b for b, e in queues_d]
+    assert max(sizes) - min(sizes) <= 1
+    # every unit carries its request's first query row and cache row
+    for u in units:
+        assert int(u[6]) == int(meta[u[0], 0]) and int(u[7]) == int(meta[u[0], 3])
     assert pod.pod_attn_workspace_size(plan) == info.workspace_bytes >= 4352
     plan.close()
     return info
