@@ -203,11 +203,29 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         }
         chunk = round_up(std::max(chunk, kDecodeStep), kDecodeStep);
         plan.decode_chunk = chunk;
+        std::vector<int> cuts;
         for (int r = prm.n_prefill; r < n_req; ++r) {
             const int kv_len = seq_meta[4 * r + 2];
             const int s = ceil_div(kv_len, chunk);
             const int tps = round_up(ceil_div(kv_len, s), kDecodeStep);
-            const int s_eff = ceil_div(kv_len, tps);
+            // Token ranges of the request: equal pieces of tps keys, except that the last piece
+            // is cut again into a half and two quarters when those are still at least 128 keys
+            // (a request that fits one piece stays whole and needs no merge).
+            // Units are claimed longest first, so the short pieces are what is left at the end of
+            // a launch, when the wavefronts that are still busy decide when it ends.
+            cuts.clear();
+            for (int t = 0; t < kv_len; t += tps) cuts.push_back(t);
+            {
+                const int t_last = cuts.back(), len = kv_len - t_last;
+                const int quarter = round_up(len / 4, kDecodeStep);
+                const int half = (len - 2 * quarter) / kDecodeStep * kDecodeStep;    // cuts stay multiples of a step
+                if (cuts.size() >= 2 && quarter >= 128 && half > 0 && half + quarter < len) {
+                    cuts.push_back(t_last + half);
+                    cuts.push_back(t_last + half + quarter);
+                }
+            }
+            cuts.push_back(kv_len);
+            const int s_eff = (int)cuts.size() - 1;
             for (int kvh = 0; kvh < prm.n_kv_heads; ++kvh) {
                 int64_t prow_base = -1;
                 if (s_eff > 1) {
@@ -219,8 +237,8 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
                 for (int i = 0; i < s_eff; ++i) {
                     DecodeUnit u;
                     u.req = r; u.kv_head = kvh;
-                    u.t0 = i * tps;
-                    u.t1 = std::min(kv_len, (i + 1) * tps);
+                    u.t0 = cuts[(size_t)i];
+                    u.t1 = cuts[(size_t)i + 1];
                     u.prow0 = s_eff > 1 ? (int32_t)(prow_base + (int64_t)i * group) : -1;
                     u.split = i; u.q_start = seq_meta[4 * r]; u.cache_row = seq_meta[4 * r + 3];
                     plan.dunits.push_back(u);

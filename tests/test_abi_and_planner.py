@@ -367,3 +367,24 @@ def test_binder_keeps_both_operations_resident_on_each_unit():
     _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
     for u in range(n_units):
         assert sorted(roles[resident[u]].tolist()) == [0, 1]
+
+
+def test_decode_last_piece_is_cut_into_half_and_quarters():
+    """The last piece of a split request is cut again (half, quarter, quarter) while the quarters
+    stay at least 128 keys; a request that fits one piece stays whole; cuts are multiples of 16."""
+    prm, meta = meta_only("taper", [], [4096, 1000, 4090, 600], hq=8, hkv=1)
+    prm.decode_chunk = 2048
+    plan = pod.pod_attn_plan_create(prm, meta)
+    pieces = {}
+    for req, kvh, t0, t1, prow0, split, _, _ in plan.decode_units():
+        pieces.setdefault(int(req), []).append((int(t0), int(t1), int(prow0)))
+    got = {r: sorted(p) for r, p in pieces.items()}
+    assert [(a, b) for a, b, _ in got[0]] == [(0, 2048), (2048, 3072), (3072, 3584), (3584, 4096)]
+    assert [(a, b) for a, b, _ in got[1]] == [(0, 1000)] and got[1][0][2] == -1
+    assert [(a, b) for a, b, _ in got[2]] == [(0, 2048), (2048, 3056), (3056, 3568), (3568, 4090)]
+    assert [(a, b) for a, b, _ in got[3]] == [(0, 600)]
+    prm.decode_chunk = 512                       # last piece of 88 keys: too short to cut again
+    plan2 = pod.pod_attn_plan_create(prm, meta)
+    last = sorted((int(u[2]), int(u[3])) for u in plan2.decode_units() if u[0] == 3)
+    assert last == [(0, 304), (304, 600)]
+    plan.close(); plan2.close()
