@@ -210,6 +210,10 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
  * switches operation if that one is exhausted.  For arrival number a, role_out[a] is 0 (prefill),
  * 1 (decode) or -1 (nothing left) and item_out[a] the claimed id (-1 if none); both arrays hold
  * one entry per arrival.  Returns the number of arrivals that got work, or -1 for bad arguments.
+ * The fused kernel picks the first operation of every resident workgroup with this same rule
+ * (the same code); on the device a workgroup then stays: it keeps claiming work of its operation
+ * and switches once when that runs out (the persistent variant of Section 4.4), so one device
+ * workgroup stands for a run of arrivals of this model.
  */
 int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items,
                                  int32_t prefill_ratio, int32_t decode_ratio,
