@@ -206,7 +206,9 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
  * created by arrival number -v - 1 (counting arrivals from 0) has finished and leaves its unit.
  * Each arrival takes a ticket from its unit's counter, picks prefill or decode so that the
  * unit's resident mix stays near prefill_ratio : decode_ratio (a tie is broken by the listing's
- * rule, ticket mod (p + d) < p means prefill), claims the next work id of that operation and
+ * rule, ticket mod (p + d) < p means prefill, where unit u counts its tickets from 2 * u so that a
+ * pattern longer than the two workgroups a unit holds is spread over the units), claims the next
+ * work id of that operation and
  * switches operation if that one is exhausted.  For arrival number a, role_out[a] is 0 (prefill),
  * 1 (decode) or -1 (nothing left) and item_out[a] the claimed id (-1 if none); both arrays hold
  * one entry per arrival.  Returns the number of arrivals that got work, or -1 for bad arguments.

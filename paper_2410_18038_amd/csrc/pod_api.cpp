@@ -359,7 +359,7 @@ int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items
         const unsigned cu = (unsigned)v & (pod::kCuSlots - 1);
         const uint32_t state = cu_state[cu];
         cu_state[cu] += pod::kTicketOne;
-        int role = pod::role_for_arrival(state, prefill_ratio, decode_ratio);
+        int role = pod::role_for_arrival(state, prefill_ratio, decode_ratio, (int)cu);
         uint32_t id = next_item[role]++;
         if (id >= limit[role]) {
             role ^= 1;

@@ -18,6 +18,7 @@ constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill ste
 constexpr int kDecodeStep = 16;            // keys per decode step of one wavefront
 constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
 constexpr int kXcdQueues = 8;               // work is queued per XCD (one L2 each); a queue's counter is claimed mostly from its own XCD
+constexpr int kSlotsPerUnit = 2;            // resident workgroups per compute unit (register and LDS budget)
 constexpr int kNullClaimLines = 512;       // power of two, at least the number of resident workgroups
 constexpr int kCuSlots = 1024;             // hardware unit ids are sparse: (xcc << 6 | se << 4 | cu) < 1024
 
@@ -82,12 +83,18 @@ constexpr uint32_t kTicketOne = 1u << 20;
 
 // Which operation an arriving workgroup should start, given the snapshot of its unit's state.
 // Keeps resident prefill : decode workgroups near p : d; a tie falls back to the ticket rule
-// of Section 4.1 (ticket mod (p + d) < p means prefill).
-POD_HD inline int role_for_arrival(uint32_t state, int p, int d)
+// of Section 4.1 (ticket mod (p + d) < p means prefill).  A unit holds only kSlotsPerUnit
+// workgroups at a time, so its own tickets would never get past the first entries of a longer
+// pattern; unit u therefore starts its tickets at kSlotsPerUnit * u, which spreads the pattern
+// over the chip (4:1 puts a decode workgroup on every fifth slot; 1:1 still gives every unit one
+// of each).  The fused kernel calls this with the resident counts masked to zero: its workgroups
+// arrive together and never leave, so the tickets alone decide, and the split does not depend on
+// which of two simultaneous arrivals is seen first.
+POD_HD inline int role_for_arrival(uint32_t state, int p, int d, int unit = 0)
 {
     const int run_p = (int)(state & 1023u);
     const int run_d = (int)((state >> 10) & 1023u);
-    const int ticket = (int)(state >> 20);
+    const int ticket = (int)(state >> 20) + kSlotsPerUnit * unit;
     const int lhs = run_p * d, rhs = run_d * p;
     if (lhs < rhs) return kPrefill;
     if (lhs > rhs) return kDecode;

@@ -25,6 +25,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define POD_LDS __attribute__((address_space(3)))
+#ifndef POD_RING
+#define POD_RING 5
+#endif
 #define POD_CONST __attribute__((address_space(4)))
 
 template <int DT> struct Num;
@@ -626,7 +629,7 @@ template <int D> struct DecodeLds {
 template <int D, int LAYOUT> struct DecodeRing {
     // registers per slot = D / 4 (K and V rows of 16 keys); about 160 registers of ring.  The
     // any-block-size layout needs per-lane 64-bit addresses and gets one slot less.
-    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 4 : 5) : 8;
+    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 4 : POD_RING) : 8;
 };
 
 // Placed right after a branch on a per-lane condition inside code that keeps wavefront-uniform
@@ -1135,7 +1138,7 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     if (threadIdx.x == 0) {
         const unsigned cu = __smid() & (kCuSlots - 1);
         const uint32_t state = atomicAdd(&hdr->cu_state[cu], kTicketOne);
-        const int role = role_for_arrival(state, a.p_ratio, a.d_ratio);
+        const int role = role_for_arrival(state & ~(kTicketOne - 1u), a.p_ratio, a.d_ratio, (int)cu);
         atomicAdd(&hdr->cu_state[cu], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
         bind[0] = role;
         bind[2] = (int)cu;
