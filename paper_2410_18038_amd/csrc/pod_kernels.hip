@@ -25,9 +25,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define POD_LDS __attribute__((address_space(3)))
-#ifndef POD_RING
-#define POD_RING 5
-#endif
 #define POD_CONST __attribute__((address_space(4)))
 
 template <int DT> struct Num;
@@ -627,9 +624,15 @@ template <int D> struct DecodeLds {
 };
 
 template <int D, int LAYOUT> struct DecodeRing {
-    // registers per slot = D / 4 (K and V rows of 16 keys); about 160 registers of ring.  The
-    // any-block-size layout needs per-lane 64-bit addresses and gets one slot less.
-    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 4 : POD_RING) : 8;
+    // A slot holds the K and V rows of 16 keys: D / 4 registers, 8 KB at D = 128.  With every
+    // wavefront slot of the chip streaming, one slot in flight per wavefront (16 MB chip-wide) is
+    // what keeps HBM busy; deeper rings only lengthen the queues in the memory system, which
+    // measured slower for the decode role itself (6.1 -> 6.3 TB/s going from 5 slots to 2 on 64
+    // requests x 32 heads x 4096 keys) and for the prefill role running beside it (its tile loads
+    // wait in the same queues).  The price: a wavefront alone on the chip streams 10.7 instead
+    // of 12.8 GB/s.  The any-block-size layout looks up block ids with vector loads before each
+    // step and gets one more slot to cover them; D = 64 slots are half the size.
+    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 3 : 2) : 4;
 };
 
 // Placed right after a branch on a per-lane condition inside code that keeps wavefront-uniform
