@@ -110,7 +110,11 @@ def test_repeated_launches_are_bit_identical_and_counters_reset():
     serial = attn.forward(dev_batch, mode=pod.MODE_SERIAL)
     assert torch.equal(first.view(torch.int16), serial.view(torch.int16))
     torch.cuda.synchronize()
-    hdr = attn.workspace[(attn.ws_ptr - attn.workspace.data_ptr()):][:4352].view(torch.int32)
+    # the whole counter block at the head of the workspace: per-unit binder state, work counters,
+    # per-XCD queue counters (one 128-byte line each) and the words that idle claims add zero to
+    hdr_bytes = 4096 + 256 + 8 * 128 + 512 * 128
+    assert attn.ws_bytes >= hdr_bytes
+    hdr = attn.workspace[(attn.ws_ptr - attn.workspace.data_ptr()):][:hdr_bytes].view(torch.int32)
     assert int(hdr.abs().sum()) == 0, "binder counters not back at zero after the launches"
     attn.close()
 
@@ -129,3 +133,75 @@ def test_decode_through_prefill_path_matches_decode_path():
     b, _ = run_gpu(as_prefill)
     assert np.abs(a - b).max() <= 2e-3
     assert np.abs(a - oracle_out(as_decode)).max() <= 2e-3
+
+
+def test_decode_stream_crosses_many_short_units():
+    """Hundreds of decode units of 1..3 steps next to a few long ones, on a plan made for two
+    compute units: few workers, so every wavefront streams through many units (the load ring then
+    holds a unit boundary most of the time, heads run out before their next unit is known, queues
+    are emptied and the other XCDs' queues are tried), in all three launch modes."""
+    rng = np.random.Generator(np.random.PCG64(321))
+    lens = rng.integers(1, 41, size=150).tolist() + [5000, 17, 3001, 1, 16, 4097]
+    for hq, hkv, d, bs in [(8, 2, 128, 16), (4, 4, 64, 0), (16, 1, 128, 48)]:
+        batch = wl.make_batch(f"stream-{hq}/{hkv}-d{d}-bs{bs}", prefill=[(70, 200)], decode_kv_lens=lens,
+                              n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=wl.F16, seed=4242 + d + bs,
+                              block_size=bs, poison=float("nan"))
+        for mode in ALL_MODES:
+            err, info = check(batch, mode, n_compute_units=2, decode_chunk=512)
+            assert info.fused_grid == 4 and info.n_decode_units > 150 * hkv
+
+
+def test_event_log_holds_every_item_and_unit_once():
+    """The event log (begin and end of every prefill item and decode unit of one launch) names each
+    work id exactly once, with sane times, and logging does not change the result."""
+    batch = wl.make_batch("evlog", prefill=[(300, 900)], decode_kv_lens=[500] * 40 + [33, 1000, 7],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.BF16, seed=99, block_size=16)
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch, decode_chunk=128)
+    plain = attn.forward(dev_batch).clone()
+    attn.enable_event_log()
+    logged = attn.forward(dev_batch)
+    ev = attn.read_event_log()
+    assert torch.equal(plain.view(torch.int16), logged.view(torch.int16))
+    assert len(ev) == attn.info.n_prefill_items + attn.info.n_decode_units
+    for kind, n in ((0, attn.info.n_prefill_items), (1, attn.info.n_decode_units)):
+        ids = np.sort(ev["item"][ev["kind"] == kind])
+        assert ids.tolist() == list(range(n))
+    assert (ev["t_end"] >= ev["t_begin"]).all()
+    span_us = (int(ev["t_end"].max()) - int(ev["t_begin"].min())) / 100.0
+    assert 0 < span_us < 1e5
+    attn.disable_event_log()
+    again = attn.forward(dev_batch)
+    assert torch.equal(plain.view(torch.int16), again.view(torch.int16))
+    attn.close()
+
+
+def _sample_rows(batch, n_p, n_d, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    npr, nd = batch.n_prefill_rows, batch.n_decode
+    fixed_p = [r for r in (0, 1, 15, 16, 127, 128, npr // 2, npr - 2, npr - 1) if 0 <= r < npr]
+    rows_p = np.unique(np.concatenate([np.array(fixed_p, dtype=np.int64), rng.integers(0, max(npr, 1), size=n_p)]))
+    rows_d = npr + np.unique(np.concatenate([np.array([0, nd - 1]), rng.integers(0, max(nd, 1), size=n_d)]))
+    return np.concatenate([rows_p[:0] if npr == 0 else rows_p, rows_d[:0] if nd == 0 else rows_d]).astype(np.int32)
+
+
+@pytest.mark.parametrize("config,index", [(2, 0), (3, 0), (4, 0), (5, 8)])
+def test_full_size_batches_on_sampled_rows(config, index):
+    """The configurations the benchmark times, at full size and with the default plan (the launch
+    shape the benchmark uses): a sample of output rows (first, last and tile-edge rows of the chunk,
+    random rows, first and last decode request; every head of each) against the oracle, in the fused
+    mode, and the serial baseline bit-identical to it."""
+    batch = wl.config_batch(config, index, device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    out = attn.forward(batch)
+    torch.cuda.synchronize()
+    rows = _sample_rows(batch, 24, 24, seed=config * 10 + index)
+    print(f"case {batch.name}: {len(rows)} sampled rows of {batch.n_rows}", flush=True)
+    want = oracle_out(batch, rows=rows)
+    got = out[torch.from_numpy(rows.astype(np.int64)).to("cuda:0")].to(torch.float64).cpu().numpy()
+    assert bool(torch.isfinite(out.to(torch.float32)).all())
+    err = np.abs(got - want).max()
+    assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} on sampled rows of {batch.name}"
+    serial = attn.forward(batch, mode=pod.MODE_SERIAL)
+    assert torch.equal(out.view(torch.int16), serial.view(torch.int16))
+    attn.close()
