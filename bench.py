@@ -27,9 +27,10 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 # HBM bytes per fused launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
 # command, scaled by the copy-kernel calibration described in the design doc; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # (config, batch_index): FETCH_SIZE 2190461.7 KiB x 2.0 (copy calibration: the counter reads
-    # half of a plain copy's bytes) + WRITE_SIZE 41650.7 KiB x 1.0, per fused launch
-    (2, 0): 4528715878,
+    # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
+    # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
+    (2, 0): 4556921651,     # 2201755.6 KiB fetched, 46607.6 KiB written
+    (4, 0): 2894058803,     # 1393360.4 KiB fetched, 39508.5 KiB written
 }
 
 
