@@ -8,6 +8,8 @@
 // wants for its P operand, and the running max and sum of a row are per-lane scalars.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "pod_common.h"
 #include "pod_launch.h"
 
@@ -472,13 +474,17 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     TileBlocks blocks_ahead = tile_blocks(2);                // for the K loads of the first iteration
     wait_all_loads();
     __syncthreads();
-    f32x16 s_cur[2], s_next[2];
-    if (it.kv_begin <= wave_maxpos) scores(0, s_cur);
+    // Two score buffers swap roles from one tile to the next; the loop body exists twice (even
+    // and odd tiles) so that the swap is a matter of names, not of 32 register moves per tile, and
+    // the LDS buffer of a tile is known at compile time.
+    f32x16 s_even[2], s_odd[2];
+    if (it.kv_begin <= wave_maxpos) scores(0, s_even);
     __syncthreads();                                         // K tile 0 is free to be overwritten
 
-    for (int jt = 0; jt < n_tiles; ++jt) {
+    auto tile_step = [&](const int jt, auto parity, f32x16 (&s_cur)[2], f32x16 (&s_next)[2])
+                         __attribute__((always_inline)) {
         const int j0 = it.kv_begin + jt * T;
-        const int cur = jt & 1;
+        constexpr int cur = decltype(parity)::value;
         // K tile jt was consumed in the previous iteration and V tile jt-1 as well (barrier below).
         TileBases fresh = carry;
         if (jt + 2 < n_tiles) {
@@ -558,8 +564,11 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         }
         wait_all_loads();                                    // K tile jt+2 and V tile jt+1 have landed
         __syncthreads();                                     // ... for every wavefront; tile jt is done
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) s_cur[tb] = s_next[tb];
+    };
+    for (int jt = 0; jt < n_tiles; jt += 2) {
+        tile_step(jt, std::integral_constant<int, 0>{}, s_even, s_odd);
+        if (jt + 1 >= n_tiles) break;
+        tile_step(jt + 1, std::integral_constant<int, 1>{}, s_odd, s_even);
     }
 
     // Epilogue.  o[mb][r] is channel mb*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
