@@ -231,6 +231,53 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     return rec
 
 
+def run_chunk_series(model, n_decode, steps, warmup, torch, pod, wl):
+    """Every chunk of a 16K prompt with the same decodes (the paper's Figure 6 / Table 8 workload):
+    per chunk the median time of the fused launch, of the serial and two-stream baselines, and of
+    two ablations of the fused launch (Section 5.4: 50:50 policy; no cap on prefill splits)."""
+    dev = "cuda:0"
+    base = wl.series_base(model, n_decode, device=dev)
+    n_chunks = wl.SERIES_PROMPT // wl.SERIES_CHUNK
+    out = torch.empty((base.n_rows, base.n_q_heads, base.head_dim), dtype=base.torch_dtype, device=dev)
+    rows = []
+    for k in range(n_chunks):
+        batch = wl.series_chunk(base, k)
+        rec = {"chunk": k, "kv_len": int(batch.seq_meta[0, 2])}
+        variants = {"fused": {}, "serial": {}, "streams": {},
+                    "fused_alternate": {"policy": pod.POLICY_ALTERNATE},
+                    "fused_uncapped": {"max_prefill_waves": 64}}
+        plans = {}
+        for name, kw in variants.items():
+            key = tuple(sorted(kw.items()))
+            if key not in plans:
+                plans[key] = pod.HybridAttention(batch, **kw)
+            attn = plans[key]
+            mode = pod.MODES[name] if name in pod.MODES else pod.MODE_FUSED
+            fn = lambda: attn.forward(batch, out=out, mode=mode)
+            for _ in range(warmup):
+                fn()
+            t = event_times_us(fn, steps, torch)
+            rec[name] = float(np.median(t))
+            if name == "fused":
+                rec["prefill_items"], rec["decode_units"] = attn.info.n_prefill_items, attn.info.n_decode_units
+                rec["ratio"] = [attn.info.prefill_ratio, attn.info.decode_ratio]
+        for attn in plans.values():
+            attn.close()
+        flops, kv_bytes = batch.prefill_flops(), batch.kv_bytes()
+        rec["roofline_us"] = max(flops / PEAK_MFMA_16BIT, kv_bytes / PEAK_HBM) * 1e6
+        rows.append(rec)
+        log(f"[series] {model} d{n_decode} chunk {k:2d} kv {rec['kv_len']:5d}: fused {rec['fused']:7.1f} serial {rec['serial']:7.1f} "
+            f"streams {rec['streams']:7.1f} | 50:50 {rec['fused_alternate']:7.1f} uncapped {rec['fused_uncapped']:7.1f} | "
+            f"roofline {rec['roofline_us']:6.1f} us")
+    tot = {k: float(sum(r[k] for r in rows)) for k in ("fused", "serial", "streams", "fused_alternate", "fused_uncapped", "roofline_us")}
+    return {"metric": "hybrid-batch attention us per batch, summed over the 32 chunks of a 16K prompt",
+            "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup, "data": "synthetic", "dtype": "bf16",
+            "config": {"workload": f"chunk-series-{model}", "chunk": wl.SERIES_CHUNK, "prompt": wl.SERIES_PROMPT,
+                       "n_decode": n_decode, "decode_ctx": wl.SERIES_DECODE_CTX, "kv_layout": "paged16"},
+            "totals_us": tot, "speedup_vs_serial": tot["serial"] / tot["fused"],
+            "pct_of_overlap_roofline": 100.0 * tot["roofline_us"] / tot["fused"], "chunks": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -245,6 +292,12 @@ def main():
                     help="only run a 1 GiB device copy and the 4 GiB read probe (known sizes, for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a profiler run) and exit")
     ap.add_argument("--sweep", default=None, help="also run every configuration and write the records to this file")
+    ap.add_argument("--chunk-series", default=None, choices=["yi-6b", "llama-3-8b"],
+                    help="instead of a configuration, time every 512-token chunk of a 16K prompt, each with "
+                         "--series-decodes decode requests at 16K context (fused, serial, two streams, and the "
+                         "fused launch with the 50:50 policy and without the prefill split cap)")
+    ap.add_argument("--series-decodes", type=int, default=64)
+    ap.add_argument("--series-out", default=None, help="write the chunk-series records to this file")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (one MI355X per box); use --gpus 1", file=sys.stderr)
@@ -266,6 +319,14 @@ def main():
         torch.cuda.synchronize()
         peaks = measure_peaks(torch, pod)
         print(json.dumps({"copy_bytes": 1 << 30, "copies": 3, "read_probe_bytes": 4 << 30, "peaks": peaks}))
+        return
+
+    if args.chunk_series:
+        rec = run_chunk_series(args.chunk_series, args.series_decodes, args.steps, args.warmup, torch, pod, wl)
+        if args.series_out:
+            with open(args.series_out, "w") as fh:
+                json.dump(rec, fh, indent=1)
+        print(json.dumps(rec), flush=True)
         return
 
     peaks = None if args.no_peaks else measure_peaks(torch, pod)

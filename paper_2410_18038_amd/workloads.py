@@ -299,3 +299,33 @@ def config_batch(config: int, batch_index: int = 0, device="cpu",
         return make_batch(f"config5-sweep-c{chunk}-d{nd}", prefill=[(chunk, 4096)], decode_kv_lens=lens,
                           n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=BF16, block_size=16, **common)
     raise ValueError("config must be 1..5")
+
+
+# ----------------------------------------------------------------------------------------------
+# Chunk series (the shape of the paper's Figure 6 and Table 8): every chunk of one long prompt,
+# each co-scheduled with the same set of decode requests.
+# ----------------------------------------------------------------------------------------------
+SERIES_MODELS = {"yi-6b": (32, 4, 128), "llama-3-8b": (32, 8, 128)}   # q heads, K/V heads, head_dim
+SERIES_PROMPT, SERIES_CHUNK, SERIES_DECODE_CTX = 16384, 512, 16384
+
+
+def series_base(model: str, n_decode: int, device="cpu", poison: Optional[float] = None) -> HybridBatch:
+    """One prompt of 16K tokens (its whole K/V in the cache) and ``n_decode`` decodes at 16K context.
+
+    ``series_chunk`` turns it into the batch of one chunk; all chunks share the tensors."""
+    hq, hkv, d = SERIES_MODELS[model]
+    seed = BASE_SEED + 100000 + 1000 * sorted(SERIES_MODELS).index(model) + n_decode
+    return make_batch(f"series-{model}-d{n_decode}", prefill=[(SERIES_CHUNK, SERIES_PROMPT)],
+                      decode_kv_lens=[SERIES_DECODE_CTX] * n_decode, n_q_heads=hq, n_kv_heads=hkv,
+                      head_dim=d, dtype=BF16, block_size=16, seed=seed, device=device, poison=poison)
+
+
+def series_chunk(base: HybridBatch, chunk_index: int) -> HybridBatch:
+    """The batch of chunk ``chunk_index`` (0-based): 512 new tokens over 512 * chunk_index cached
+    ones.  The query values are those of the base batch; only the visible length changes."""
+    n_chunks = SERIES_PROMPT // SERIES_CHUNK
+    if not 0 <= chunk_index < n_chunks:
+        raise ValueError("chunk_index out of range")
+    meta = base.seq_meta.copy()
+    meta[0, 2] = SERIES_CHUNK * (chunk_index + 1)
+    return dataclasses.replace(base, name=f"{base.name}-chunk{chunk_index}", seq_meta=meta)

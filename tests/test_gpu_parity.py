@@ -205,3 +205,24 @@ def test_full_size_batches_on_sampled_rows(config, index):
     serial = attn.forward(batch, mode=pod.MODE_SERIAL)
     assert torch.equal(out.view(torch.int16), serial.view(torch.int16))
     attn.close()
+
+
+@pytest.mark.parametrize("model,n_decode,chunk", [("yi-6b", 54, 0), ("yi-6b", 55, 31), ("llama-3-8b", 64, 15)])
+def test_chunk_series_batches_on_sampled_rows(model, n_decode, chunk):
+    """Chunks of a 16K prompt next to decodes at 16K context (the shape of the paper's Figure 6 and
+    Table 8; 54 and 55 decodes are its wave-quantization pair): sampled rows against the oracle."""
+    base = wl.series_base(model, n_decode, device="cuda:0")
+    batch = wl.series_chunk(base, chunk)
+    attn = pod.HybridAttention(batch)
+    out = attn.forward(batch)
+    torch.cuda.synchronize()
+    rows = _sample_rows(batch, 16, 16, seed=chunk + n_decode)
+    print(f"case {batch.name}: {len(rows)} sampled rows of {batch.n_rows}", flush=True)
+    want = oracle_out(batch, rows=rows)
+    got = out[torch.from_numpy(rows.astype(np.int64)).to("cuda:0")].to(torch.float64).cpu().numpy()
+    err = np.abs(got - want).max()
+    assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} on sampled rows of {batch.name}"
+    for mode in ("serial", "streams"):
+        other = attn.forward(batch, mode=pod.MODES[mode])
+        assert torch.equal(out.view(torch.int16), other.view(torch.int16))
+    attn.close()
