@@ -231,6 +231,59 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     return rec
 
 
+def run_colocation(steps, warmup, torch, pod):
+    """Section 3.2's experiment on this GPU: 8192 compute items and 8192 memory items (c = a + b over
+    1 GiB per array), the compute loop sized to take as long as the memory operation alone."""
+    dev = "cuda:0"
+    n_items, item_bytes = 8192, 128 << 10
+    a = torch.ones(n_items * item_bytes // 4, dtype=torch.float32, device=dev)
+    b = torch.full_like(a, 2.0)
+    c = torch.zeros_like(a)
+    ctr = torch.zeros(1026, dtype=torch.int32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    side = torch.cuda.Stream(device=dev)
+
+    def launch(variant, iters, n_mem=n_items, n_cmp=n_items, stream=None):
+        st = (stream or torch.cuda.current_stream(dev)).cuda_stream
+        pod.pod_attn_probe_colocation(variant, a.data_ptr(), b.data_ptr(), c.data_ptr(), item_bytes, n_mem, n_cmp,
+                                      iters, ctr.data_ptr(), sink.data_ptr(), st)
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        return float(np.median(event_times_us(fn, steps, torch)))
+
+    t_mem = timed(lambda: launch(1, 0))
+    iters = 2048
+    t_cmp = timed(lambda: launch(0, iters))
+    iters = max(64, int(iters * t_mem / t_cmp))
+    t_cmp = timed(lambda: launch(0, iters))
+
+    def two_streams():
+        main = torch.cuda.current_stream(dev)
+        side.wait_stream(main)
+        launch(0, iters)
+        launch(1, 0, stream=side)
+        main.wait_stream(side)
+
+    res = {"compute_alone": t_cmp, "memory_alone": t_mem,
+           "serial": timed(lambda: (launch(0, iters), launch(1, 0))),
+           "streams": timed(two_streams),
+           "fused_by_index": timed(lambda: launch(2, iters)),
+           "fused_bound_per_unit": timed(lambda: launch(3, iters))}
+    torch.cuda.synchronize()
+    ok = bool((c == 3.0).all())
+    moved = 3 * n_items * item_bytes
+    log("[colocation] " + ", ".join(f"{k} {v:.1f} us" for k, v in res.items()) + f"; c == a + b: {ok}")
+    return {"metric": "co-location experiment (Section 3.2), us per run", "unit": "us", "n_gpus": 1, "steps": steps,
+            "warmup": warmup, "data": "synthetic", "dtype": "f32",
+            "config": {"workload": "colocation", "compute_items": n_items, "memory_items": n_items,
+                       "bytes_moved": moved, "compute_iters": iters},
+            "times_us": res, "memory_alone_GBps": moved / t_mem / 1e3, "result_ok": ok,
+            "speedup_bound_vs_serial": res["serial"] / res["fused_bound_per_unit"],
+            "speedup_by_index_vs_serial": res["serial"] / res["fused_by_index"]}
+
+
 def run_chunk_series(model, n_decode, steps, warmup, torch, pod, wl):
     """Every chunk of a 16K prompt with the same decodes (the paper's Figure 6 / Table 8 workload):
     per chunk the median time of the fused launch, of the serial and two-stream baselines, and of
@@ -296,6 +349,10 @@ def main():
                     help="instead of a configuration, time every 512-token chunk of a 16K prompt, each with "
                          "--series-decodes decode requests at 16K context (fused, serial, two streams, and the "
                          "fused launch with the 50:50 policy and without the prefill split cap)")
+    ap.add_argument("--colocation", action="store_true",
+                    help="instead of a configuration, run the co-location experiment of the paper's Section 3.2: "
+                         "a compute-bound and a memory-bound operation serially, on two streams, fused by "
+                         "workgroup index and fused with per-compute-unit binding")
     ap.add_argument("--series-decodes", type=int, default=64)
     ap.add_argument("--series-out", default=None, help="write the chunk-series records to this file")
     args = ap.parse_args()
@@ -321,6 +378,9 @@ def main():
         print(json.dumps({"copy_bytes": 1 << 30, "copies": 3, "read_probe_bytes": 4 << 30, "peaks": peaks}))
         return
 
+    if args.colocation:
+        print(json.dumps(run_colocation(args.steps, args.warmup, torch, pod)), flush=True)
+        return
     if args.chunk_series:
         rec = run_chunk_series(args.chunk_series, args.series_decodes, args.steps, args.warmup, torch, pod, wl)
         if args.series_out:

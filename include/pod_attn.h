@@ -256,6 +256,26 @@ pod_status pod_attn_plan_decode_queue(const pod_attn_plan *plan, int32_t q, int3
 pod_status pod_attn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *stream);
 pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, void *stream);
 
+/*
+ * The co-location experiment of Section 3.2 (Figure 7), independent of attention: a compute-bound
+ * operation (n_compute_items workgroups' worth of multiply-add loops, compute_iters rounds each)
+ * and a memory-bound one (c = a + b over n_memory_items chunks of bytes_per_item bytes per array),
+ * launched as
+ *   variant 0: the compute operation alone          variant 1: the memory operation alone
+ *   variant 2: one kernel, operation chosen by workgroup index (compute first)
+ *   variant 3: one kernel, operation bound at run time per compute unit as in Section 4.1
+ *              (ticket from that unit's counter, alternate operations, claim the next item).
+ * a, b, c: device arrays of n_memory_items * bytes_per_item bytes (bytes_per_item a multiple of
+ * 16); counters: 4104 bytes of device memory, needed by variant 3 only, which clears them on the
+ * stream itself (with a memset: do not capture this call in a graph); sink: 4 writable bytes.
+ * Serial execution is variants 0 and 1 on one stream, "streams" the same two on two streams.
+ * Asynchronous on `stream`.  Returns POD_ERR_INVALID_ARG for bad arguments.
+ */
+pod_status pod_attn_probe_colocation(int32_t variant, const void *a, const void *b, void *c,
+                                     size_t bytes_per_item, int32_t n_memory_items,
+                                     int32_t n_compute_items, int32_t compute_iters, void *counters,
+                                     void *sink, void *stream);
+
 const char *pod_attn_last_error(void);
 const char *pod_attn_version(void);
 

@@ -1,6 +1,8 @@
-// Two micro-kernels that measure what this GPU can sustain: a coalesced HBM read stream and an
-// MFMA issue loop.  The benchmark reports the attention kernels against these measured peaks
-// next to the datasheet ones.
+// Micro-kernels.  Two measure what this GPU can sustain: a coalesced HBM read stream and an MFMA
+// issue loop; the benchmark reports the attention kernels against these measured peaks next to
+// the datasheet ones.  A third group is the co-location experiment of the paper's Section 3.2
+// (a compute-bound and a memory-bound operation, run one after the other, fused by workgroup
+// index, and fused with roles bound per compute unit at run time).
 #include <hip/hip_runtime.h>
 
 #include "../../include/pod_attn.h"
@@ -10,6 +12,7 @@ namespace {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
 constexpr int kUnroll = 8;
@@ -50,6 +53,94 @@ __global__ __launch_bounds__(kThreads) void mfma_loop_kernel(int iters, float *s
     if (s == 12345.678f) sink[0] = s;
 }
 
+// ---- co-location experiment (Section 3.2, Figure 7) -------------------------------------------
+// Compute item: every thread runs `iters` rounds of eight independent multiply-adds.  Memory
+// item: c = a + b over a chunk of n_vec 16-byte vectors, coalesced.  Both use 256 threads and
+// few registers, so eight workgroups of either kind fit on a compute unit.
+struct ColoArgs {
+    const f32x4 *a, *b;
+    f32x4 *c;
+    uint32_t *ctr;                  // [1024] per-unit tickets, then [2] next item of each kind
+    float *sink;
+    uint32_t n_vec;                 // vectors per memory item
+    int32_t n_cmp, n_mem, iters;
+};
+
+__device__ __forceinline__ void colo_compute(const ColoArgs &g, int item)
+{
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.001f * (float)(threadIdx.x + i + item);
+    const float m = 1.0000001f, d = 1e-7f;
+    for (int it = 0; it < g.iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = __builtin_fmaf(x[i], m, d);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += x[i];
+    if (s == 12345.678f) g.sink[0] = s;
+}
+
+__device__ __forceinline__ void colo_memory(const ColoArgs &g, int item)
+{
+    const size_t base = (size_t)item * g.n_vec;
+    for (uint32_t i = threadIdx.x; i < g.n_vec; i += 4 * kThreads) {
+        f32x4 va[4], vb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = i + u * kThreads;
+            if (j < g.n_vec) {
+                va[u] = __builtin_nontemporal_load(g.a + base + j);
+                vb[u] = __builtin_nontemporal_load(g.b + base + j);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t j = i + u * kThreads;
+            if (j < g.n_vec) {
+                const f32x4 r = va[u] + vb[u];
+                __builtin_nontemporal_store(r, g.c + base + j);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void colo_compute_kernel(ColoArgs g) { colo_compute(g, blockIdx.x); }
+__global__ __launch_bounds__(kThreads) void colo_memory_kernel(ColoArgs g) { colo_memory(g, blockIdx.x); }
+
+// Fusion by workgroup index: the first n_cmp workgroups compute, the rest move memory.  Which
+// compute unit a workgroup lands on, and when, is the hardware's choice.
+__global__ __launch_bounds__(kThreads) void colo_fused_by_index_kernel(ColoArgs g)
+{
+    if ((int)blockIdx.x < g.n_cmp) colo_compute(g, blockIdx.x);
+    else colo_memory(g, blockIdx.x - g.n_cmp);
+}
+
+// Fusion with run-time binding (Section 4.1): the workgroup asks which compute unit it is on,
+// takes that unit's next ticket, alternates between the two operations by ticket parity, claims
+// the next item of its operation, and takes the other operation's work when its own has run out.
+__global__ __launch_bounds__(kThreads) void colo_fused_bound_kernel(ColoArgs g)
+{
+    __shared__ int pick[2];
+    if (threadIdx.x == 0) {
+        const unsigned cu = __smid() & 1023u;
+        const uint32_t ticket = atomicAdd(&g.ctr[cu], 1u);
+        int role = (int)(ticket & 1u);                       // 0 compute, 1 memory
+        int item = (int)atomicAdd(&g.ctr[1024 + role], 1u);
+        if (item >= (role == 0 ? g.n_cmp : g.n_mem)) {
+            role ^= 1;
+            item = (int)atomicAdd(&g.ctr[1024 + role], 1u);
+            if (item >= (role == 0 ? g.n_cmp : g.n_mem)) role = -1;
+        }
+        pick[0] = role;
+        pick[1] = item;
+    }
+    __syncthreads();
+    if (pick[0] == 0) colo_compute(g, pick[1]);
+    else if (pick[0] == 1) colo_memory(g, pick[1]);
+}
+
 }  // namespace
 
 extern "C" {
@@ -74,6 +165,44 @@ pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, voi
     const int grid = cus * 2;                       // 8 wavefronts per compute unit, 2 per SIMD
     mfma_loop_kernel<<<dim3(grid), dim3(kThreads), 0, (hipStream_t)stream>>>(iters, (float *)sink);
     if (flops_out) *flops_out = (double)grid * (kThreads / 64) * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+    return hipGetLastError() == hipSuccess ? POD_OK : POD_ERR_HIP;
+}
+
+pod_status pod_attn_probe_colocation(int32_t variant, const void *a, const void *b, void *c,
+                                     size_t bytes_per_item, int32_t n_memory_items,
+                                     int32_t n_compute_items, int32_t compute_iters, void *counters,
+                                     void *sink, void *stream)
+{
+    if (variant < 0 || variant > 3 || !sink) return POD_ERR_INVALID_ARG;
+    if (n_memory_items < 0 || n_compute_items < 0 || compute_iters < 0) return POD_ERR_INVALID_ARG;
+    if (bytes_per_item % 16 != 0 || bytes_per_item / 16 > 0xffffffffull) return POD_ERR_INVALID_ARG;
+    const bool uses_memory = variant != 0 && n_memory_items > 0;
+    if (uses_memory && (!a || !b || !c)) return POD_ERR_INVALID_ARG;
+    if (variant == 3 && !counters) return POD_ERR_INVALID_ARG;
+    ColoArgs g;
+    g.a = (const f32x4 *)a; g.b = (const f32x4 *)b; g.c = (f32x4 *)c;
+    g.ctr = (uint32_t *)counters; g.sink = (float *)sink;
+    g.n_vec = (uint32_t)(bytes_per_item / 16);
+    g.n_cmp = n_compute_items; g.n_mem = n_memory_items; g.iters = compute_iters;
+    hipStream_t s = (hipStream_t)stream;
+    const int n_both = n_compute_items + n_memory_items;
+    switch (variant) {
+    case 0:
+        if (n_compute_items > 0) colo_compute_kernel<<<dim3(n_compute_items), dim3(kThreads), 0, s>>>(g);
+        break;
+    case 1:
+        if (n_memory_items > 0) colo_memory_kernel<<<dim3(n_memory_items), dim3(kThreads), 0, s>>>(g);
+        break;
+    case 2:
+        if (n_both > 0) colo_fused_by_index_kernel<<<dim3(n_both), dim3(kThreads), 0, s>>>(g);
+        break;
+    default:
+        if (n_both > 0) {
+            if (hipMemsetAsync(counters, 0, 1026 * sizeof(uint32_t), s) != hipSuccess) return POD_ERR_HIP;
+            colo_fused_bound_kernel<<<dim3(n_both), dim3(kThreads), 0, s>>>(g);
+        }
+        break;
+    }
     return hipGetLastError() == hipSuccess ? POD_OK : POD_ERR_HIP;
 }
 

@@ -28,7 +28,7 @@ EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_
            "pod_attn_plan_upload", "pod_attn_forward",
            "pod_attn_simulate_binder", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
            "pod_attn_plan_decode_queue",
-           "pod_attn_probe_hbm_read", "pod_attn_probe_mfma",
+           "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_colocation",
            "pod_attn_last_error", "pod_attn_version"]
 
 
@@ -110,6 +110,9 @@ def lib():
         L.pod_attn_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.pod_attn_probe_mfma.restype = ctypes.c_int
         L.pod_attn_probe_mfma.argtypes = [ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pod_attn_probe_colocation.restype = ctypes.c_int
+        L.pod_attn_probe_colocation.argtypes = [ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32,
+                                                ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
         L.pod_attn_last_error.restype = ctypes.c_char_p
         L.pod_attn_version.restype = ctypes.c_char_p
         _lib = L
@@ -259,6 +262,13 @@ def pod_attn_probe_mfma(iters: int, sink: int, stream: int = 0) -> float:
     if status != POD_OK:
         raise PodError(status, "pod_attn_probe_mfma failed")
     return float(flops.value)
+
+
+def pod_attn_probe_colocation(variant: int, a: int, b: int, c: int, bytes_per_item: int, n_memory_items: int,
+                              n_compute_items: int, compute_iters: int, counters: int, sink: int, stream: int = 0):
+    _check(lib().pod_attn_probe_colocation(variant, ctypes.c_void_p(a), ctypes.c_void_p(b), ctypes.c_void_p(c),
+                                           bytes_per_item, n_memory_items, n_compute_items, compute_iters,
+                                           ctypes.c_void_p(counters), ctypes.c_void_p(sink), ctypes.c_void_p(stream)))
 
 
 def pod_attn_simulate_binder(n_prefill_items: int, n_decode_items: int, prefill_ratio: int,

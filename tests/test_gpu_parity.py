@@ -226,3 +226,26 @@ def test_chunk_series_batches_on_sampled_rows(model, n_decode, chunk):
         other = attn.forward(batch, mode=pod.MODES[mode])
         assert torch.equal(out.view(torch.int16), other.view(torch.int16))
     attn.close()
+
+
+def test_colocation_probe_moves_every_chunk_once():
+    """The co-location experiment (Section 3.2): every variant of the fused launch computes c = a + b
+    over every chunk exactly once, whatever the binding, and the per-unit binder claims every item."""
+    n_items, item_bytes = 700, 16 * 1000
+    a = torch.arange(n_items * item_bytes // 4, dtype=torch.float32, device="cuda:0")
+    b = torch.full_like(a, 0.5)
+    ctr = torch.zeros(1026, dtype=torch.int32, device="cuda:0")
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+    for variant, n_cmp in [(1, 0), (2, 300), (3, 300), (3, 0), (3, 1500)]:
+        c = torch.zeros_like(a)
+        pod.pod_attn_probe_colocation(variant, a.data_ptr(), b.data_ptr(), c.data_ptr(), item_bytes, n_items, n_cmp,
+                                      50, ctr.data_ptr(), sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.equal(c, a + b), f"variant {variant} with {n_cmp} compute items"
+        if variant == 3:
+            got = ctr.cpu().numpy()
+            assert got[:1024].sum() == n_items + n_cmp
+            assert got[1024] >= n_cmp and got[1025] >= n_items and got[1024] + got[1025] <= n_items + n_cmp + 2 * (n_items + n_cmp)
+    with pytest.raises(pod.PodError):
+        pod.pod_attn_probe_colocation(3, a.data_ptr(), b.data_ptr(), a.data_ptr(), 24, 1, 1, 1, ctr.data_ptr(),
+                                      sink.data_ptr(), 0)
