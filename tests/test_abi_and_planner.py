@@ -403,3 +403,21 @@ def test_binder_spreads_a_long_pattern_over_the_units():
     assert first.tolist() == [0 if (2 * u) % 5 < 4 else 1 for u in range(n_units)]
     _, roles11, _ = pod.pod_attn_simulate_binder(10 ** 6, 10 ** 6, 1, 1, events)
     assert all(sorted(roles11[2 * u:2 * u + 2].tolist()) == [0, 1] for u in range(n_units))
+
+
+def test_event_log_and_queue_arguments_are_checked():
+    """Host-side checks only (no GPU call): the event log must be 16-byte aligned and hold at least
+    one record; a decode queue index must be 0..7."""
+    prm, meta = meta_only("args", [(64, 64)], [100, 200])
+    plan = pod.pod_attn_plan_create(prm, meta)
+    with pytest.raises(pod.PodError):
+        pod.pod_attn_plan_set_event_log(plan, 4096, 40)          # too small
+    with pytest.raises(pod.PodError):
+        pod.pod_attn_plan_set_event_log(plan, 4096 + 8, 4096)    # misaligned
+    pod.pod_attn_plan_set_event_log(plan, 4096, 4096)            # accepted (never dereferenced here)
+    pod.pod_attn_plan_set_event_log(plan, 0, 0)                  # off again
+    for q in (-1, 8):
+        with pytest.raises(pod.PodError):
+            pod.pod_attn_plan_decode_queue(plan, q)
+    assert len(plan.decode_queues()) == 8
+    plan.close()
