@@ -149,6 +149,13 @@ def test_decode_stream_crosses_many_short_units():
         for mode in ALL_MODES:
             err, info = check(batch, mode, n_compute_units=2, decode_chunk=512)
             assert info.fused_grid == 4 and info.n_decode_units > 150 * hkv
+    # and a plan made for more compute units than the GPU has: more workgroups than can be resident
+    # at once, so some start only when others have left
+    batch = wl.make_batch("oversubscribed", prefill=[(700, 1400)], decode_kv_lens=[300] * 900 + [2000] * 8,
+                          n_q_heads=8, n_kv_heads=4, head_dim=128, dtype=wl.BF16, seed=777, block_size=16)
+    for mode in ALL_MODES:
+        err, info = check(batch, mode, n_compute_units=1000, decode_chunk=128)
+        assert info.fused_grid == 2000
 
 
 def test_event_log_holds_every_item_and_unit_once():
