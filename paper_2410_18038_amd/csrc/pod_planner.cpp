@@ -204,6 +204,13 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         chunk = round_up(std::max(chunk, kDecodeStep), kDecodeStep);
         plan.decode_chunk = chunk;
         std::vector<int> cuts;
+        {
+            size_t n_est = 0;
+            for (int r = prm.n_prefill; r < n_req; ++r)
+                n_est += (size_t)prm.n_kv_heads * (size_t)(seq_meta[4 * r + 2] / chunk + 3);
+            plan.dunits.reserve(n_est);
+            plan.centries.reserve(plan.centries.size() + (size_t)prm.n_decode * prm.n_kv_heads);
+        }
         for (int r = prm.n_prefill; r < n_req; ++r) {
             const int kv_len = seq_meta[4 * r + 2];
             const int s = ceil_div(kv_len, chunk);
@@ -273,6 +280,11 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     plan.n_partial_rows = next_prow;
 
     // One (entry, row) pair per output row that is merged from partials, prefill entries first.
+    {
+        size_t n_pairs = 0;
+        for (const CombineEntry &c : plan.centries) n_pairs += (size_t)c.n_rows;
+        plan.crows.reserve(2 * n_pairs);
+    }
     for (size_t e = 0; e < plan.centries.size(); ++e) {
         const CombineEntry &c = plan.centries[e];
         for (int r = 0; r < c.n_rows; ++r) {
