@@ -191,6 +191,10 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  * The device arrays are trusted: a seq_meta that differs from the planned one, or a block
  * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode, optionally OR-ed with
  * POD_MODE_FLAG_NO_COMBINE.
+ * The call only launches kernels on `stream` (no allocation, no memset, no wait on the host), so
+ * in the FUSED, SERIAL and single-operation modes it may be recorded into a HIP graph; the
+ * STREAMS mode creates its two side streams and events on first use and is not meant for capture.
+ * Two forward calls that use the same workspace must not overlap in time.
  */
 pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
                             const void *k_cache, const void *v_cache,

@@ -256,3 +256,35 @@ def test_colocation_probe_moves_every_chunk_once():
     with pytest.raises(pod.PodError):
         pod.pod_attn_probe_colocation(3, a.data_ptr(), b.data_ptr(), a.data_ptr(), 24, 1, 1, 1, ctr.data_ptr(),
                                       sink.data_ptr(), 0)
+
+
+@pytest.mark.parametrize("mode", ["fused", "serial"])
+def test_forward_can_be_captured_in_a_graph_and_replayed(mode):
+    """`pod_attn_forward` launches kernels only (no allocation, no memset, no host wait), so a caller
+    may record it into a HIP graph.  Replays, with eager launches and synchronisations between them,
+    give the eager result bit for bit, and the counters are back at zero after each."""
+    batch = wl.make_batch("graph", prefill=[(200, 700)], decode_kv_lens=[900] * 30 + [64, 2500],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.F16, seed=31, block_size=16)
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch, decode_chunk=256)
+    eager = attn.forward(dev_batch, mode=pod.MODES[mode]).clone()
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        attn.forward(dev_batch, out=out, mode=pod.MODES[mode])        # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            attn.forward(dev_batch, out=out, mode=pod.MODES[mode])
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(4):
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {i}"
+        again = attn.forward(dev_batch, mode=pod.MODES[mode])              # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(again.view(torch.int16), eager.view(torch.int16))
+    attn.close()
