@@ -608,17 +608,15 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 // ------------------------------------------------------------------------------------------
 // Decode path (Section 4.2.3: a decode workgroup is cut into one-wavefront virtual units, so
 // no workgroup barrier is used here).  A wavefront is a persistent worker over a stream of decode
-// units.  It reads K and V rows once from HBM with fully coalesced 16-byte loads; the rows of the
-// next kRing-1 steps (16 keys each) are in flight in a ring of registers, which is where the
-// bytes-in-flight needed to cover HBM latency live: the fused kernel's register budget is set by
-// the prefill role, and the decode role spends it on this ring.  The ring runs on across unit
-// boundaries: the "head" (the step being requested from memory) moves into the next unit while
-// the "tail" (the step being computed) finishes the current one, so a boundary costs no drained
-// pipeline.  For that the next unit is claimed, its descriptor read and its query heads copied
-// to LDS a couple of ring turns before the head needs them.  A small wavefront-private LDS region
-// turns 16 rows at a time into MFMA operands.  The query heads of the group are the (zero
-// padded) 16 columns of the products, so the matrix unit is busy for a few percent of the time
-// only (Section 4.2.1).
+// units.  It reads K and V rows once from HBM with fully coalesced 16-byte loads, in steps of 16
+// keys; while one step is computed the next ones are in flight in a short ring of registers.
+// The ring runs on across unit boundaries: the "head" (the step being requested from memory)
+// moves into the next unit while the "tail" (the step being computed) finishes the current one,
+// so a boundary costs no drained pipeline.  For that the next unit is claimed, its descriptor
+// read and its query heads copied to LDS a few steps before the head needs them.  A small
+// wavefront-private LDS region turns 16 rows at a time into MFMA operands.  The query heads of
+// the group are the (zero padded) 16 columns of the products, so the matrix unit is busy for a
+// few percent of the time only (Section 4.2.1).
 // ------------------------------------------------------------------------------------------
 template <int D> struct DecodeLds {
     static constexpr int kKStride = D * 2 + 16;
