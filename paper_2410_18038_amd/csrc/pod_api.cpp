@@ -74,15 +74,6 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
         while ((1 << s) < p.prm.block_size) ++s;
         a.bs_shift = s;
     }
-    a.tok_shift = -1;
-    {
-        const int tok_bytes = p.prm.n_kv_heads * p.prm.head_dim * 2;
-        if ((tok_bytes & (tok_bytes - 1)) == 0) {
-            int sh = 0;
-            while ((1 << sh) < tok_bytes) ++sh;
-            a.tok_shift = sh;
-        }
-    }
     a.n_pitems = (int)p.pitems.size();
     a.n_dunits = (int)p.dunits.size();
     a.n_dwgs = p.n_dwgs;

@@ -141,7 +141,6 @@ struct KernelArgs {
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;
     int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1
-    int32_t tok_shift;                     // log2(bytes per cached token = Hkv*d*2) when a power of two, else -1
     int32_t n_crows;
     int32_t n_pitems, n_dunits, n_dwgs, n_combine;   // n_dwgs: decode worker workgroups
     int32_t n_prefill_rows;

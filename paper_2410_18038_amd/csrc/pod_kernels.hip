@@ -365,12 +365,14 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) tb.b[p] = off;
         } else if constexpr (LAYOUT == kLayoutPaged16) {
-            // block size and bytes per token are powers of two in this layout: shifts only
+            // the block size is a power of two in this layout; bytes per token need not be (the
+            // K/V head count of a model or of its tensor-parallel shard can be 5, 6, 10, 40 ...)
+            const uint32_t block_bytes = (uint32_t)tok_bytes << a.bs_shift;
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 const uint32_t t = (uint32_t)(j0 + p * RPP + wave * RPW);
-                const uint64_t block_off = (uint64_t)(uint32_t)blk.id[p] << (a.bs_shift + a.tok_shift);
-                const uint64_t row_off = (uint64_t)((t & (uint32_t)(a.block_size - 1)) << a.tok_shift);
+                const uint64_t block_off = (uint64_t)(uint32_t)blk.id[p] * block_bytes;
+                const uint64_t row_off = (uint64_t)((t & (uint32_t)(a.block_size - 1)) * (uint32_t)tok_bytes);
                 tb.b[p] = (int64_t)(blocks16 ? block_off : block_off + row_off);
             }
         } else {
@@ -379,7 +381,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         }
         return tb;
     };
-    // Fast path for a full tile of the contiguous and power-of-two paged layouts.
+    // Fast path for a full tile of the contiguous layout and of paged layouts with power-of-two blocks.
     auto issue_fast = [&](const TileBases &tb, int buf, bool is_k) {
         const char *src = is_k ? (const char *)kc : (const char *)vc;
 #pragma unroll
@@ -1301,8 +1303,9 @@ static hipError_t launch_layout(int which, const KernelArgs &a, int layout, hipS
 
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
 {
-    const int layout = !paged ? kLayoutContiguous
-                              : (a.bs_shift >= 4 && a.tok_shift >= 0 ? kLayoutPaged16 : kLayoutPagedAny);
+    // The block-wise paths want power-of-two blocks of at least 16 keys whose byte size fits 32 bits.
+    const bool block_wise = a.bs_shift >= 4 && (((int64_t)a.n_kv_heads * head_dim * 2) << a.bs_shift) < (1ll << 32);
+    const int layout = !paged ? kLayoutContiguous : (block_wise ? kLayoutPaged16 : kLayoutPagedAny);
     if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, layout, stream);
     if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);
     if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, layout, stream);

@@ -76,6 +76,20 @@ def test_shapes_dtypes_layouts(dtype, hq, hkv, d, block_size):
     check(batch, "fused")
 
 
+@pytest.mark.parametrize("hq,hkv", [(5, 5), (9, 3), (10, 5)])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("block_size", [0, 16, 64, 24])
+def test_token_sizes_that_are_no_power_of_two(hq, hkv, d, block_size):
+    """K/V head counts of 3 and 5: a cached token of 768 ... 2560 bytes, in the contiguous layout,
+    the block-wise paged layouts (16 and 64 keys) and the general one (24 keys)."""
+    batch = wl.make_batch(f"odd-{hq}/{hkv}-d{d}-bs{block_size}", prefill=[(150, 401), (64, 64)],
+                          decode_kv_lens=[1, 47, 48, 49, 300, 1111], n_q_heads=hq, n_kv_heads=hkv,
+                          head_dim=d, dtype=wl.F16, seed=2000 + hq * 7 + hkv + d + block_size,
+                          block_size=block_size, poison=float("nan"))
+    check(batch, "fused")
+    check(batch, "serial", decode_chunk=256, prefill_split_len=128, max_prefill_waves=64)
+
+
 @pytest.mark.parametrize("mode", ALL_MODES)
 @pytest.mark.parametrize("block_size", [0, 16, 48])
 def test_split_kv_paths(mode, block_size):
