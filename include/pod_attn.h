@@ -72,6 +72,13 @@ typedef enum {
     POD_POLICY_PROPORTIONAL = 2 /* in the ratio of prefill to decode work of this batch          */
 } pod_policy;
 
+/* Order of the two middle dimensions of the cache.  The paper does not fix a cache layout; both
+ * orders in use by serving systems are accepted. */
+typedef enum {
+    POD_KV_TOKEN_MAJOR = 0,     /* [..][token][Hkv][d]: a token's heads lie together               */
+    POD_KV_HEAD_MAJOR = 1       /* [..][Hkv][token][d]: a head's tokens lie together               */
+} pod_kv_order;
+
 typedef struct {
     int32_t n_prefill;          /* prefill requests (may be 0)                                   */
     int32_t n_decode;           /* decode requests (may be 0)                                    */
@@ -91,6 +98,8 @@ typedef struct {
     int32_t decode_chunk;       /* tokens per decode work unit (split-KV length); 0 = automatic  */
     int32_t prefill_split_len;  /* minimum keys per prefill split; 0 = automatic                 */
     int32_t n_compute_units;    /* 0 = ask the current device (256 on MI355X if none is present) */
+    int32_t kv_order;           /* pod_kv_order; with POD_KV_HEAD_MAJOR a contiguous cache needs
+                                   kv_seq_stride to be a multiple of Hkv*d (= max_len*Hkv*d)     */
 } pod_attn_params;
 
 /* Counts that describe a plan; filled by pod_attn_plan_info. */
@@ -179,6 +188,9 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  *   k_cache,    contiguous: [n_cache_rows][max_len][Hkv][d] with kv_seq_stride elements
  *   v_cache                 between sequences;
  *               paged:      [n_blocks][block_size][Hkv][d]
+ *               with kv_order = POD_KV_HEAD_MAJOR the two middle dimensions change places:
+ *               [n_cache_rows][Hkv][max_len][d] (max_len = kv_seq_stride / (Hkv*d)) and
+ *               [n_blocks][Hkv][block_size][d]
  *   seq_meta    device copy of the array given to pod_attn_plan_create
  *   block_table paged: int32 [n_cache_rows][max_blocks_per_seq], entry [row][t / block_size]
  *               is the physical block of token t (token t sits at offset t % block_size);

@@ -23,7 +23,8 @@
  *   - Query head h reads K/V head h / (Hq / Hkv) (contiguous groups).
  *   - Cache layouts: contiguous [seq][token][Hkv][d] with a per-sequence
  *     stride, or paged [block][block_size][Hkv][d] resolved through
- *     block_table[cache_row][token / block_size].
+ *     block_table[cache_row][token / block_size]; in the head-major variant of
+ *     either, the token and head dimensions change places.
  *
  * Method: the plain definition, written out.  Two-pass softmax (all scores,
  * then their maximum, then the weights), no tiling, no online rescaling, no
@@ -85,20 +86,30 @@ typedef struct {
     const int32_t *block_table;
     int n_kv_heads, head_dim, block_size, max_blocks_per_seq;
     int64_t kv_seq_stride;
+    int head_major;
 } cache_view;
 
-/* Element offset of token `t` of cache row `row`, K/V head `kvh`, channel 0. */
+/* Element offset of token `t` of cache row `row`, K/V head `kvh`, channel 0.
+ * The cache is a 4-d array [outer][n_mid0][n_mid1][d]: `outer` is the sequence or
+ * the physical block, `slot` the token's place inside it and `n_slots` its
+ * capacity in tokens; (mid0, mid1) = (slot, head) or, head-major, (head, slot). */
 static int64_t cache_offset(const cache_view *c, int row, int t, int kvh)
 {
-    int64_t token_elems = (int64_t)c->n_kv_heads * c->head_dim;
-    int64_t base;
+    int64_t outer_elems, slot, n_slots, outer;
     if (c->block_size > 0) {
-        int64_t blk = c->block_table[(int64_t)row * c->max_blocks_per_seq + t / c->block_size];
-        base = (blk * c->block_size + t % c->block_size) * token_elems;
+        outer = c->block_table[(int64_t)row * c->max_blocks_per_seq + t / c->block_size];
+        slot = t % c->block_size;
+        n_slots = c->block_size;
+        outer_elems = n_slots * c->n_kv_heads * c->head_dim;
     } else {
-        base = (int64_t)row * c->kv_seq_stride + (int64_t)t * token_elems;
+        outer = row;
+        slot = t;
+        outer_elems = c->kv_seq_stride;
+        n_slots = c->kv_seq_stride / ((int64_t)c->n_kv_heads * c->head_dim);
     }
-    return base + (int64_t)kvh * c->head_dim;
+    if (c->head_major)
+        return outer * outer_elems + ((int64_t)kvh * n_slots + slot) * c->head_dim;
+    return outer * outer_elems + (slot * c->n_kv_heads + kvh) * c->head_dim;
 }
 
 /*
@@ -118,6 +129,7 @@ int pod_oracle_attention(const uint16_t *prefill_q, const uint16_t *decode_q,
                          int n_q_heads, int n_kv_heads, int head_dim, int dtype,
                          double softmax_scale,
                          int block_size, int max_blocks_per_seq, int64_t kv_seq_stride,
+                         int head_major,
                          const int32_t *rows, int64_t n_rows,
                          double *out)
 {
@@ -165,7 +177,7 @@ int pod_oracle_attention(const uint16_t *prefill_q, const uint16_t *decode_q,
         widen[b] = pod_oracle_widen(dtype, (uint16_t)b);
 
     cache_view cv = { k_cache, v_cache, block_table, n_kv_heads, head_dim,
-                      block_size, max_blocks_per_seq, kv_seq_stride };
+                      block_size, max_blocks_per_seq, kv_seq_stride, head_major != 0 };
     const int64_t n_work = (rows ? n_rows : n_total) * n_q_heads;
     int failed = 0;
 

@@ -46,7 +46,7 @@ def _load():
         lib.pod_oracle_attention.argtypes = [
             u16p, u16p, u16p, u16p, i32p, i32p,
             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-            ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int64,
+            ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
             i32p, ctypes.c_int64, ctypes.POINTER(ctypes.c_double)]
         lib.pod_oracle_widen.restype = ctypes.c_double
         lib.pod_oracle_widen.argtypes = [ctypes.c_int, ctypes.c_uint16]
@@ -84,7 +84,7 @@ def _i32(a: Optional[np.ndarray]):
 def attention(prefill_q_bits, decode_q_bits, k_bits, v_bits, seq_meta, block_table, *,
               n_prefill: int, n_decode: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
               dtype: int, softmax_scale: float, block_size: int = 0,
-              max_blocks_per_seq: int = 0, kv_seq_stride: int = 0,
+              max_blocks_per_seq: int = 0, kv_seq_stride: int = 0, head_major: bool = False,
               rows=None) -> np.ndarray:
     """Oracle output as float64 ``[rows, Hq, d]``.
 
@@ -92,6 +92,7 @@ def attention(prefill_q_bits, decode_q_bits, k_bits, v_bits, seq_meta, block_tab
     ``[n_prefill + n_decode, 4]`` = ``(q_start, q_len, kv_len, cache_row)``, prefill
     requests first.  Output rows are the prefill rows followed by one row per decode
     request.  With ``rows`` (global output row indices) only those rows are computed.
+    ``head_major``: the cache is [.., Hkv, tokens, d] instead of [.., tokens, Hkv, d].
     """
     lib = _load()
     seq_meta = np.ascontiguousarray(seq_meta, dtype=np.int32).reshape(-1, 4)
@@ -118,7 +119,7 @@ def attention(prefill_q_bits, decode_q_bits, k_bits, v_bits, seq_meta, block_tab
     rc = lib.pod_oracle_attention(
         ptrs[0], ptrs[1], ptrs[2], ptrs[3], meta_ptr, bt_ptr,
         n_prefill, n_decode, n_q_heads, n_kv_heads, head_dim, dtype,
-        float(softmax_scale), block_size, max_blocks_per_seq, kv_seq_stride,
+        float(softmax_scale), block_size, max_blocks_per_seq, kv_seq_stride, int(bool(head_major)),
         rows_ptr, n_rows, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     if rc != 0:
         raise ValueError(f"pod_oracle_attention rejected its arguments (code {rc})")

@@ -62,6 +62,17 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.part_o = (float *)(ws + p.off_part_o);
     a.part_ml = (float *)(ws + p.off_part_ml);
     a.kv_seq_stride = p.prm.kv_seq_stride;
+    {
+        const int64_t d = p.prm.head_dim, hkv = p.prm.n_kv_heads, bs = p.prm.block_size;
+        a.block_elems = bs * hkv * d;
+        if (p.prm.kv_order == POD_KV_HEAD_MAJOR) {
+            a.tok_stride = (int32_t)d;
+            a.head_stride = bs > 0 ? bs * d : p.prm.kv_seq_stride / (hkv * d) * d;
+        } else {
+            a.tok_stride = (int32_t)(hkv * d);
+            a.head_stride = d;
+        }
+    }
     a.n_prefill = p.prm.n_prefill;
     a.n_q_heads = p.prm.n_q_heads;
     a.n_kv_heads = p.prm.n_kv_heads;

@@ -138,6 +138,11 @@ struct KernelArgs {
     uint32_t *evlog;                       // optional: event log (16-byte header, then EventRecords)
     uint32_t evlog_cap;                    // records the event log can hold
     int64_t kv_seq_stride;
+    // Cache strides in elements, the same three for the token-major and the head-major order:
+    // between consecutive tokens of one head, between the heads of a sequence (or of a block), and
+    // between blocks of a paged cache.
+    int64_t head_stride, block_elems;
+    int32_t tok_stride;
     int32_t n_prefill, n_q_heads, n_kv_heads, group;
     int32_t block_size, max_blocks_per_seq;
     int32_t bs_shift;                      // log2(block_size) when it is a power of two, else -1

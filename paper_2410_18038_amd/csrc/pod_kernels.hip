@@ -114,7 +114,9 @@ __device__ __forceinline__ s16x4 lds_read_tr(const POD_LDS unsigned char *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((POD_LDS s16x4 *)p);
 }
 
-// Element offset (head 0, channel 0) of token t of a cache row.
+// Element offset (head 0, channel 0) of token t of a cache row.  Both cache orders go through the
+// same three strides: elements between the tokens of a head, between the heads of a sequence or
+// block (added by the callers), and between blocks.
 template <bool PAGED>
 __device__ __forceinline__ int64_t token_offset(const KernelArgs &a, int cache_row, int t, int token_elems)
 {
@@ -123,7 +125,7 @@ __device__ __forceinline__ int64_t token_offset(const KernelArgs &a, int cache_r
         if (a.bs_shift >= 0) { bi = t >> a.bs_shift; off = t & (a.block_size - 1); }
         else { bi = t / a.block_size; off = t - bi * a.block_size; }
         const int blk = a.block_table[(int64_t)cache_row * a.max_blocks_per_seq + bi];
-        return ((int64_t)blk * a.block_size + off) * token_elems;
+        return (int64_t)blk * a.block_elems + (int64_t)off * token_elems;
     } else {
         return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
     }
@@ -256,7 +258,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     const int q_start = meta[0], q_len = meta[1], kv_len = meta[2], cache_row = meta[3];
     const int prefix = kv_len - q_len;
     const int group = a.group;
-    const int token_elems = a.n_kv_heads * D;
+    const int token_elems = a.tok_stride;           // elements between consecutive tokens of a head
     const int rows_total = q_len * group;
 
     // This lane's query row.
@@ -319,8 +321,8 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         v_src[p] = (uint32_t)(src_row * tok_bytes + v_swizzle<D>(row, wr_pos) * 16);
     }
 
-    const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * D;
-    const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * D;
+    const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * a.head_stride;
+    const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * a.head_stride;
     const POD_CONST int32_t *table = (const POD_CONST int32_t *)a.block_table +
                                      (int64_t)cache_row * a.max_blocks_per_seq;
     const int n_tiles = (it.kv_end - it.kv_begin + T - 1) / T;
@@ -367,7 +369,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         } else if constexpr (LAYOUT == kLayoutPaged16) {
             // the block size is a power of two in this layout; bytes per token need not be (the
             // K/V head count of a model or of its tensor-parallel shard can be 5, 6, 10, 40 ...)
-            const uint32_t block_bytes = (uint32_t)tok_bytes << a.bs_shift;
+            const uint32_t block_bytes = (uint32_t)a.block_elems * 2u;
 #pragma unroll
             for (int p = 0; p < NPASS; ++p) {
                 const uint32_t t = (uint32_t)(j0 + p * RPP + wave * RPW);
@@ -419,7 +421,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                     base = (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * token_elems;
                 } else {
                     const int blk = table[t >> a.bs_shift];
-                    base = ((int64_t)blk * a.block_size + (t & (a.block_size - 1))) * token_elems;
+                    base = (int64_t)blk * a.block_elems + (int64_t)(t & (a.block_size - 1)) * token_elems;
                 }
                 const int lrow = row_base + wr_row;
                 const int rl = min(lrow, last_row) - base_eff;
@@ -682,7 +684,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     const int n16 = lane & 15;                     // query column (head within the group)
     const int b4 = lane >> 4;
     const int group = a.group;
-    const int token_elems = a.n_kv_heads * D;
+    const int token_elems = a.tok_stride;           // elements between consecutive tokens of a head
     const bool col_ok = n16 < group;
     const float c = a.scale_log2;
     const int ld_row = lane / CH, ld_chunk = lane % CH;
@@ -799,7 +801,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
             // block_size is a power of two >= 16 and t a multiple of 16: a step never straddles blocks
             const int bi = t >> a.bs_shift, off = t & (a.block_size - 1);
             const int blk = table[bi];
-            return ((int64_t)blk * a.block_size + off) * token_elems;
+            return (int64_t)blk * a.block_elems + (int64_t)off * token_elems;
         } else {
             return 0;
         }
@@ -808,8 +810,8 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
         hu = d;
         h_t = d.t0;
         h_addr_t = d.t0;
-        kc = (const elem *)a.k_cache + d.kv_head * D;
-        vc = (const elem *)a.v_cache + d.kv_head * D;
+        kc = (const elem *)a.k_cache + d.kv_head * a.head_stride;
+        vc = (const elem *)a.v_cache + d.kv_head * a.head_stride;
         table = (const POD_CONST int32_t *)a.block_table + (int64_t)d.cache_row * a.max_blocks_per_seq;
         h_base = base_of(d.cache_row, d.t0);
         set_voff(d.t0, d.t1);
@@ -1304,7 +1306,7 @@ static hipError_t launch_layout(int which, const KernelArgs &a, int layout, hipS
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream)
 {
     // The block-wise paths want power-of-two blocks of at least 16 keys whose byte size fits 32 bits.
-    const bool block_wise = a.bs_shift >= 4 && (((int64_t)a.n_kv_heads * head_dim * 2) << a.bs_shift) < (1ll << 32);
+    const bool block_wise = a.bs_shift >= 4 && a.block_elems * 2 < (1ll << 32);
     const int layout = !paged ? kLayoutContiguous : (block_wise ? kLayoutPaged16 : kLayoutPagedAny);
     if (dtype == 0 && head_dim == 128) return launch_layout<0, 128>(which, a, layout, stream);
     if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);

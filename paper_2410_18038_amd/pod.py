@@ -22,6 +22,7 @@ MODE_FLAG_NO_COMBINE = 0x100
 MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
          "prefill_only": MODE_PREFILL_ONLY, "decode_only": MODE_DECODE_ONLY}
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
+KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
            "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_set_event_log",
@@ -47,7 +48,7 @@ class Params(ctypes.Structure):
                 ("n_blocks", ctypes.c_int32), ("kv_seq_stride", ctypes.c_int64),
                 ("policy", ctypes.c_int32), ("max_prefill_waves", ctypes.c_int32),
                 ("decode_chunk", ctypes.c_int32), ("prefill_split_len", ctypes.c_int32),
-                ("n_compute_units", ctypes.c_int32)]
+                ("n_compute_units", ctypes.c_int32), ("kv_order", ctypes.c_int32)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -174,10 +175,10 @@ class Plan:
 def make_params(*, n_prefill, n_decode, n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale,
                 block_size=0, max_blocks_per_seq=0, n_cache_rows=1, n_blocks=0, kv_seq_stride=0,
                 policy=POLICY_AUTO, max_prefill_waves=0, decode_chunk=0, prefill_split_len=0,
-                n_compute_units=0) -> Params:
+                n_compute_units=0, kv_order=KV_TOKEN_MAJOR) -> Params:
     return Params(n_prefill, n_decode, n_q_heads, n_kv_heads, head_dim, dtype, softmax_scale,
                   block_size, max_blocks_per_seq, n_cache_rows, n_blocks, kv_seq_stride, policy,
-                  max_prefill_waves, decode_chunk, prefill_split_len, n_compute_units)
+                  max_prefill_waves, decode_chunk, prefill_split_len, n_compute_units, kv_order)
 
 
 def pod_attn_plan_create(params: Params, seq_meta_host) -> Plan:
@@ -303,7 +304,8 @@ class HybridAttention:
             max_blocks_per_seq=batch.max_blocks_per_seq, n_cache_rows=batch.n_cache_rows,
             n_blocks=batch.n_blocks, kv_seq_stride=batch.kv_seq_stride, policy=policy,
             max_prefill_waves=max_prefill_waves, decode_chunk=decode_chunk,
-            prefill_split_len=prefill_split_len, n_compute_units=n_compute_units)
+            prefill_split_len=prefill_split_len, n_compute_units=n_compute_units,
+            kv_order=KV_HEAD_MAJOR if batch.head_major else KV_TOKEN_MAJOR)
         self.plan = pod_attn_plan_create(self.params, self.batch_meta)
         self.info = self.plan.info()
         dev = batch.k_cache.device

@@ -31,7 +31,8 @@ class HybridBatch:
     seq_meta: int32 [n_prefill + n_decode, 4] = (q_start, q_len, kv_len, cache_row),
     prefill requests first.  Contiguous cache: [n_seqs, max_len, Hkv, d]; paged
     cache: [n_blocks, block_size, Hkv, d] with block_table [n_seqs, max_blocks_per_seq]
-    (entries past a sequence's last block are -1).
+    (entries past a sequence's last block are -1).  With ``head_major`` the two middle
+    dimensions of either cache change places: [.., Hkv, tokens, d].
     """
     name: str
     n_prefill: int
@@ -53,6 +54,7 @@ class HybridBatch:
     k_cache: torch.Tensor
     v_cache: torch.Tensor
     block_table: Optional[torch.Tensor]
+    head_major: bool = False
 
     @property
     def n_prefill_rows(self) -> int:
@@ -185,6 +187,15 @@ def make_batch(name: str, *, prefill: Sequence[Tuple[int, int]], decode_kv_lens:
                        n_cache_rows=max(n_seqs, 1), n_blocks=n_blocks, max_len=cap, seq_meta=meta,
                        prefill_q=prefill_q, decode_q=decode_q, k_cache=k_cache, v_cache=v_cache,
                        block_table=block_table)
+
+
+def to_head_major(batch: HybridBatch) -> HybridBatch:
+    """The same batch with a head-major cache ([.., Hkv, tokens, d]); values are moved, never changed."""
+    if batch.head_major:
+        return batch
+    return dataclasses.replace(batch, name=batch.name + "/head-major", head_major=True,
+                               k_cache=batch.k_cache.transpose(1, 2).contiguous(),
+                               v_cache=batch.v_cache.transpose(1, 2).contiguous())
 
 
 def regroup(batch: HybridBatch, block_size: int, seed: int, poison: Optional[float] = None

@@ -15,12 +15,14 @@ def oracle_out(batch: wl.HybridBatch, rows=None) -> np.ndarray:
         n_kv_heads=batch.n_kv_heads, head_dim=batch.head_dim, dtype=batch.dtype,
         softmax_scale=batch.softmax_scale, block_size=batch.block_size,
         max_blocks_per_seq=batch.max_blocks_per_seq, kv_seq_stride=batch.kv_seq_stride,
-        rows=rows)
+        head_major=batch.head_major, rows=rows)
 
 
 def logical_kv(batch: wl.HybridBatch, req: int):
     """float64 (K, V) of one request as [kv_len, Hkv, d], resolved through the layout."""
     _, _, kv_len, row = (int(x) for x in batch.seq_meta[req])
+    if batch.head_major:
+        raise ValueError("logical_kv reads token-major caches only")
     if batch.block_size > 0:
         tbl = batch.block_table.cpu().numpy()
         t = np.arange(kv_len)

@@ -63,15 +63,16 @@ def test_struct_layouts_match_the_header(tmp_path):
     src = tmp_path / "sizes.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "pod_attn.h"\n'
-        'int main(void){printf("%zu %zu %zu %zu %zu\\n", sizeof(pod_attn_params), sizeof(pod_attn_plan_info),'
+        'int main(void){printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(pod_attn_params), sizeof(pod_attn_plan_info),'
         ' offsetof(pod_attn_params, kv_seq_stride), offsetof(pod_attn_params, n_compute_units),'
-        ' offsetof(pod_attn_plan_info, workspace_bytes)); return 0;}\n')
+        ' offsetof(pod_attn_params, kv_order), offsetof(pod_attn_plan_info, workspace_bytes)); return 0;}\n')
     exe = tmp_path / "sizes"
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
                    check=True)
     got = [int(x) for x in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
     assert got == [ctypes.sizeof(pod.Params), ctypes.sizeof(pod.PlanInfo), pod.Params.kv_seq_stride.offset,
-                   pod.Params.n_compute_units.offset, pod.PlanInfo.workspace_bytes.offset]
+                   pod.Params.n_compute_units.offset, pod.Params.kv_order.offset,
+                   pod.PlanInfo.workspace_bytes.offset]
 
 
 # -- validation ------------------------------------------------------------------------------- #
@@ -93,6 +94,9 @@ def test_invalid_arguments_are_rejected_with_a_message():
     expect(-1, params_for(b, softmax_scale=0.0))
     expect(-1, params_for(b, softmax_scale=float("nan")))
     expect(-1, params_for(b, kv_seq_stride=0))
+    expect(-1, params_for(b, kv_order=2))
+    expect(-1, params_for(b, kv_order=pod.KV_HEAD_MAJOR, kv_seq_stride=b.kv_seq_stride + 8))   # no whole token count
+    pod.pod_attn_plan_create(params_for(b, kv_order=pod.KV_HEAD_MAJOR), b.seq_meta).close()
     expect(-1, params_for(b, block_size=16, max_blocks_per_seq=0))
     for col, val in [(1, 0), (2, 100), (3, 99), (0, -1)]:          # q_len 0; kv_len < q_len; row; q_start
         m = b.seq_meta.copy()

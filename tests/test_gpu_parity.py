@@ -90,6 +90,19 @@ def test_token_sizes_that_are_no_power_of_two(hq, hkv, d, block_size):
     check(batch, "serial", decode_chunk=256, prefill_split_len=128, max_prefill_waves=64)
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d", [(wl.F16, 8, 2, 128), (wl.BF16, 6, 3, 64), (wl.F16, 4, 4, 128)])
+@pytest.mark.parametrize("block_size", [0, 16, 32, 24])
+def test_head_major_cache(dtype, hq, hkv, d, block_size):
+    """The [.., Hkv, tokens, d] cache order in every address path: contiguous, block-wise paged
+    (16 and 32 keys) and general paged (24 keys); unseen slots poisoned."""
+    batch = wl.to_head_major(wl.make_batch(
+        f"hm-{hq}/{hkv}-d{d}-bs{block_size}", prefill=[(150, 401), (64, 64)],
+        decode_kv_lens=[1, 47, 48, 49, 300, 1111], n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=dtype,
+        seed=3000 + hq * 7 + hkv + d + block_size, block_size=block_size, poison=float("nan")))
+    check(batch, "fused")
+    check(batch, "serial", decode_chunk=256, prefill_split_len=128, max_prefill_waves=64)
+
+
 @pytest.mark.parametrize("mode", ALL_MODES)
 @pytest.mark.parametrize("block_size", [0, 16, 48])
 def test_split_kv_paths(mode, block_size):

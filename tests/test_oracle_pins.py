@@ -119,6 +119,23 @@ def test_paged_and_contiguous_layouts_agree_exactly(dtype):
         np.testing.assert_array_equal(oracle_out(back), ref)
 
 
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+def test_head_major_and_token_major_caches_agree_exactly(dtype):
+    """The head-major cache is the token-major one with its two middle axes swapped (here by a
+    numpy-style transpose, not by the oracle's offset rule): identical values, identical output.
+    Three K/V heads against 33 or 4 slots: a swapped stride reads another head or a poisoned slot."""
+    b = small_batch(dtype=dtype, hq=6, hkv=3, d=16, prefill=((7, 21),), decodes=(1, 16, 17, 33),
+                    poison=float("nan"))
+    ref = oracle_out(b)
+    hm = wl.to_head_major(b)
+    assert hm.head_major and hm.k_cache.shape[1] == 3 and hm.k_cache.shape[2] == b.k_cache.shape[1]
+    np.testing.assert_array_equal(oracle_out(hm), ref)
+    for bs in (1, 4, 16):
+        paged = wl.to_head_major(wl.regroup(b, bs, seed=7 + bs, poison=float("nan")))
+        assert paged.k_cache.shape[1:3] == (3, bs)
+        np.testing.assert_array_equal(oracle_out(paged), ref)
+
+
 # -- p6: closed form with zero queries -------------------------------------------- #
 def test_zero_query_gives_running_mean_and_exact_causal_boundary():
     """Q = 0 makes every weight equal; with V[j] = j the answer is pos / 2.
