@@ -219,7 +219,7 @@ def _sample_rows(batch, n_p, n_d, seed):
     return np.concatenate([rows_p[:0] if npr == 0 else rows_p, rows_d[:0] if nd == 0 else rows_d]).astype(np.int32)
 
 
-@pytest.mark.parametrize("config,index", [(2, 0), (3, 0), (4, 0), (5, 8)])
+@pytest.mark.parametrize("config,index", [(2, 0), (3, 0), (4, 0)] + [(5, i) for i in range(len(wl.RATIO_SWEEP))])
 def test_full_size_batches_on_sampled_rows(config, index):
     """The configurations the benchmark times, at full size and with the default plan (the launch
     shape the benchmark uses): a sample of output rows (first, last and tile-edge rows of the chunk,
