@@ -178,7 +178,14 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         // the workgroups that re-read that head's K/V tiles share an L2 and the re-reads do not
         // reach HBM.  Inside a queue: longest first, since ids are claimed in order.  A worker
         // whose own queue is empty takes items from the other queues.
-        auto queue_of = [&](const PrefillItem &x) { return (x.req * prm.n_kv_heads + x.kv_head) % kXcdQueues; };
+        // With fewer (request, K/V head) streams than queues, a stream's row blocks are dealt over
+        // several queues, so that every XCD has a queue of its own to start from.
+        const int n_streams = prm.n_prefill * prm.n_kv_heads;
+        const int per = n_streams > 0 && n_streams < kXcdQueues ? kXcdQueues / n_streams : 1;
+        auto queue_of = [&](const PrefillItem &x) {
+            const int stream = x.req * prm.n_kv_heads + x.kv_head;
+            return (stream * per + (x.row0 / kPrefillRows) % per) % kXcdQueues;
+        };
         std::stable_sort(plan.pitems.begin(), plan.pitems.end(), [&](const PrefillItem &x, const PrefillItem &y) {
             const int qx = queue_of(x), qy = queue_of(y);
             if (qx != qy) return qx < qy;

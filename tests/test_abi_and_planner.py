@@ -178,8 +178,12 @@ def coverage_check(prm, meta):
     for a, b in zip(spans, spans[1:]):
         assert a[1] <= b[0]
     assert (spans[-1][1] if spans else 0) <= info.n_partial_rows
-    # prefill items: one queue per XCD (K/V head modulo 8), queues in order, longest first inside a queue
-    queues = [int(i[0] * prm.n_kv_heads + i[1]) % 8 for i in items]
+    # prefill items: one queue per XCD ((request, K/V head) stream modulo 8; with fewer streams than
+    # queues a stream's row blocks are dealt over 8 / streams queues), queues in order, longest
+    # first inside a queue
+    n_streams = prm.n_prefill * prm.n_kv_heads
+    per = 8 // n_streams if 0 < n_streams < 8 else 1
+    queues = [(int(i[0] * prm.n_kv_heads + i[1]) * per + (int(i[2]) // 128) % per) % 8 for i in items]
     assert queues == sorted(queues)
     for q in set(queues):
         lens = [int(i[5] - i[4]) for i, qq in zip(items, queues) if qq == q]
