@@ -200,6 +200,8 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  *               decode request in decode_q order; rounded to nearest-even from fp32.
  *   workspace   as prepared by pod_attn_plan_upload with this plan.
  *
+ * The 16-bit arrays must be 16-byte aligned (rows are read and written in 16-byte pieces; a
+ * contiguous cache also needs kv_seq_stride to be a multiple of 8 elements), else POD_ERR_INVALID_ARG.
  * The device arrays are trusted: a seq_meta that differs from the planned one, or a block
  * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode, optionally OR-ed with
  * POD_MODE_FLAG_NO_COMBINE.

@@ -264,6 +264,11 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     if (paged && !block_table) return fail(POD_ERR_INVALID_ARG, "block_table is null for a paged cache");
     if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
     if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    // every row is read and written in 16-byte pieces
+    if ((((uintptr_t)prefill_q | (uintptr_t)decode_q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u) != 0)
+        return fail(POD_ERR_INVALID_ARG, "prefill_q, decode_q, k_cache, v_cache and out must be 16-byte aligned");
+    if ((((uintptr_t)seq_meta | (uintptr_t)block_table) & 3u) != 0)
+        return fail(POD_ERR_INVALID_ARG, "seq_meta and block_table must be 4-byte aligned");
 
     pod::KernelArgs a = make_args(p, prefill_q, decode_q, k_cache, v_cache, seq_meta, block_table, out, workspace);
     hipStream_t s = (hipStream_t)stream;

@@ -68,6 +68,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         return POD_ERR_INVALID_ARG;
     }
     if (!paged && prm.kv_seq_stride <= 0) { err = "contiguous cache needs kv_seq_stride"; return POD_ERR_INVALID_ARG; }
+    if (!paged && prm.kv_seq_stride % 8 != 0) { err = "kv_seq_stride must be a multiple of 8 elements (rows are read in 16-byte pieces)"; return POD_ERR_INVALID_ARG; }
     if (prm.kv_order != POD_KV_TOKEN_MAJOR && prm.kv_order != POD_KV_HEAD_MAJOR) { err = "unknown kv_order"; return POD_ERR_INVALID_ARG; }
     if (!paged && prm.kv_order == POD_KV_HEAD_MAJOR && prm.kv_seq_stride % ((int64_t)prm.n_kv_heads * prm.head_dim) != 0) {
         err = "head-major contiguous cache: kv_seq_stride must be a multiple of n_kv_heads * head_dim";

@@ -95,6 +95,7 @@ def test_invalid_arguments_are_rejected_with_a_message():
     expect(-1, params_for(b, softmax_scale=float("nan")))
     expect(-1, params_for(b, kv_seq_stride=0))
     expect(-1, params_for(b, kv_order=2))
+    expect(-1, params_for(b, kv_seq_stride=b.kv_seq_stride + 4))                                 # rows off 16 bytes
     expect(-1, params_for(b, kv_order=pod.KV_HEAD_MAJOR, kv_seq_stride=b.kv_seq_stride + 8))   # no whole token count
     pod.pod_attn_plan_create(params_for(b, kv_order=pod.KV_HEAD_MAJOR), b.seq_meta).close()
     expect(-1, params_for(b, block_size=16, max_blocks_per_seq=0))
@@ -125,6 +126,9 @@ def test_forward_rejects_missing_buffers_without_touching_the_gpu():
     with pytest.raises(pod.PodError) as e:
         pod.pod_attn_forward(8, 8, 8, 8, 8, 0, 8, plan, 256, 1 << 30, mode=9)
     assert e.value.status == -1
+    with pytest.raises(pod.PodError) as e:                     # rows must be 16-byte aligned: rejected before any launch
+        pod.pod_attn_forward(8, 8, 8, 8, 8, 0, 8, plan, 256, 1 << 30)
+    assert e.value.status == -1 and "aligned" in str(e.value)
     plan.close()
 
 
