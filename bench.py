@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 PEAK_MFMA_16BIT = 2.5e15        # dense fp16/bf16 MFMA flop/s, MI355X
 PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 # HBM bytes per fused launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same
-# command, scaled by the copy-kernel calibration described in the design doc; None = not measured.
+# command, scaled by what the same counters read for a plain device copy of known size; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
