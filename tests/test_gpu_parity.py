@@ -114,6 +114,22 @@ def test_split_kv_paths(mode, block_size):
     assert info.max_prefill_splits > 1 and info.max_decode_splits > 1
 
 
+@pytest.mark.parametrize("block_size", [0, 16])
+def test_many_requests_of_both_kinds(block_size):
+    """Forty prefill chunks (1..300 new tokens over 0..900 cached ones) and 1500 decodes (1..700
+    keys) in one batch, every output row against the oracle: request tables, row blocks that mix
+    nothing across requests, thousands of short decode units and their queues."""
+    rng = np.random.Generator(np.random.PCG64(4242 + block_size))
+    prefill = [(int(q), int(q + p)) for q, p in zip(rng.integers(1, 301, 40), rng.integers(0, 901, 40))]
+    decodes = rng.integers(1, 701, 1500).tolist()
+    batch = wl.make_batch(f"many-bs{block_size}", prefill=prefill, decode_kv_lens=decodes, n_q_heads=16,
+                          n_kv_heads=4, head_dim=128, dtype=wl.BF16, seed=4243 + block_size,
+                          block_size=block_size, poison=float("nan"))
+    err, info = check(batch, "fused")
+    assert info.n_decode_units >= 1500 * 4 and info.n_prefill_items >= 40 * 4
+    check(batch, "serial")
+
+
 def test_degenerate_batches():
     """Only prefill, only decode, one key, a chunk without prefix."""
     for name, prefill, decodes in [("only-prefill", [(65, 65)], []), ("only-decode", [], [1, 5, 64]),
