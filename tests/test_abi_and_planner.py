@@ -269,6 +269,32 @@ def test_ragged_and_degenerate_batches_plan_cleanly():
     plan.close()
 
 
+def test_random_batches_and_tuning_values_plan_cleanly():
+    """120 seeded random batches (0..5 chunks, 0..60 decodes, lengths 1..20000, 1..16 heads per
+    group) under random tuning values and chip sizes: every plan passes the coverage check."""
+    rng = np.random.Generator(np.random.PCG64(20241018))
+    for case in range(120):
+        n_p, n_d = int(rng.integers(0, 6)), int(rng.integers(0, 61))
+        if n_p + n_d == 0:
+            n_d = 1
+        top = int(rng.choice([40, 700, 20000]))
+        prefill = []
+        for _ in range(n_p):
+            kv = int(rng.integers(1, top + 1))
+            prefill.append((int(rng.integers(1, min(kv, 3000) + 1)), kv))
+        decodes = rng.integers(1, top + 1, n_d).tolist()
+        hkv = int(rng.choice([1, 2, 3, 5, 8]))
+        group = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        prm, meta = meta_only(f"rand{case}", prefill, decodes, hq=hkv * group, hkv=hkv,
+                              d=int(rng.choice([64, 128])), block_size=int(rng.choice([0, 16])))
+        prm.n_compute_units = int(rng.choice([1, 2, 7, 64, 256, 304]))
+        prm.decode_chunk = int(rng.choice([0, 0, 16, 100, 256, 4096]))
+        prm.prefill_split_len = int(rng.choice([0, 0, 64, 300, 1 << 20]))
+        prm.max_prefill_waves = int(rng.choice([0, 1, 2, 64]))
+        prm.policy = int(rng.integers(0, 3))
+        coverage_check(prm, meta)
+
+
 # -- role ratio and the binder model -------------------------------------------------------------- #
 def read_golden(name):
     rows = []

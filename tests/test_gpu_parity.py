@@ -130,6 +130,35 @@ def test_many_requests_of_both_kinds(block_size):
     check(batch, "serial")
 
 
+def test_random_batches_and_tuning_values():
+    """Thirty seeded random batches (shapes, layouts, lengths) under random split lengths, split
+    caps, policies and planned chip sizes, in a random mode each: all rows against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(777))
+    for case in range(30):
+        n_p, n_d = int(rng.integers(0, 4)), int(rng.integers(0, 40))
+        if n_p + n_d == 0:
+            n_p = 1
+        top = int(rng.choice([60, 600, 3000]))
+        prefill = []
+        for _ in range(n_p):
+            kv = int(rng.integers(1, top + 1))
+            prefill.append((int(rng.integers(1, min(kv, 400) + 1)), kv))
+        decodes = rng.integers(1, top + 1, n_d).tolist()
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        group = int(rng.choice([1, 2, 4, 7, 16]))
+        dtype = int(rng.choice([wl.F16, wl.BF16]))
+        batch = wl.make_batch(f"rand{case}", prefill=prefill, decode_kv_lens=decodes, n_q_heads=hkv * group,
+                              n_kv_heads=hkv, head_dim=int(rng.choice([64, 128])), dtype=dtype,
+                              seed=7000 + case, block_size=int(rng.choice([0, 16, 32, 40])), poison=float("nan"))
+        if rng.integers(0, 2):
+            batch = wl.to_head_major(batch)
+        kw = dict(n_compute_units=int(rng.choice([0, 1, 3, 64, 500])),
+                  decode_chunk=int(rng.choice([0, 16, 112, 256, 1024])),
+                  prefill_split_len=int(rng.choice([0, 64, 320])),
+                  max_prefill_waves=int(rng.choice([0, 1, 64])), policy=int(rng.integers(0, 3)))
+        check(batch, str(rng.choice(ALL_MODES)), **kw)
+
+
 def test_degenerate_batches():
     """Only prefill, only decode, one key, a chunk without prefix."""
     for name, prefill, decodes in [("only-prefill", [(65, 65)], []), ("only-decode", [], [1, 5, 64]),
