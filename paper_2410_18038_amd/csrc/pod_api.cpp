@@ -90,8 +90,9 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.n_dwgs = p.n_dwgs;
     a.fused_grid = p.fused_grid;
     for (int q = 0; q <= pod::kXcdQueues; ++q) a.pq_begin[q] = p.pq_begin[q];
-    // Every workgroup of a launch with decode work takes a decode seat sooner or later, so all
-    // fixed units are run whatever operation the workgroups start with.
+    // Every workgroup of a launch with decode work asks for a decode seat sooner or later and the
+    // grid is never smaller than the number of seats, so all fixed units are run whatever
+    // operation the workgroups start with.
     a.dq_begin = (const int32_t *)(ws + p.off_dq);
     a.n_static_seats = p.n_static_seats;
     a.n_combine = (int)p.centries.size();

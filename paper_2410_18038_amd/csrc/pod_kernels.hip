@@ -291,17 +291,19 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // kTileBytes, V buffers at 2 and 3 times kTileBytes.
     POD_LDS unsigned char *const lds = (POD_LDS unsigned char *)smem;
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;       // LDS byte address of the region
-    // readers: byte offsets inside a tile, without the compile-time row blocks
-    uint32_t k_rd[KS], v_rd[MB];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        k_rd[ks] = (uint32_t)(n32 * L::kRowBytes + k_swizzle<D>(n32, 2 * ks + h) * 16);
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+    // readers: byte offsets inside a tile, without the compile-time row blocks.  The swizzles are
+    // XORs of the chunk index, so slice ks of K sits at k_rd0 ^ (ks << 5) and block mb of V at
+    // v_rd0 ^ (mb << 6): one register each, and one XOR with a constant at the point of use
+    // (eight registers fewer than a table of addresses, which this loop needs for its LDS reads
+    // in flight).
+    const uint32_t k_rd0 = (uint32_t)(n32 * L::kRowBytes + k_swizzle<D>(n32, h) * 16);
+    uint32_t v_rd0;
+    {
         const int row = 4 * h + (i16 >> 2);
-        const int c = mb * 4 + b16 * 2 + ((i16 & 3) >> 1);
-        v_rd[mb] = (uint32_t)(row * L::kRowBytes + v_swizzle<D>(row, c) * 16 + (i16 & 1) * 8);
+        const int c = b16 * 2 + ((i16 & 3) >> 1);
+        v_rd0 = (uint32_t)(row * L::kRowBytes + v_swizzle<D>(row, c) * 16 + (i16 & 1) * 8);
     }
+    static_assert((D == 128 || D == 64) && KS * 32 <= L::kRowBytes && MB * 64 <= L::kRowBytes, "swizzle algebra");
     // writers: this lane's LDS chunk in pass p is row p*RPP + wave*RPW + lane/CH, position lane%CH.
     // Lane offsets (bytes) of the source chunk for full tiles.  Contiguous cache: relative to the
     // tile's first row.  Paged cache: relative to the first row of this wavefront's rows in the
@@ -445,16 +447,35 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // Register r of block tb holds key j0 + tb*32 + 8*(r/4) + 4*h + r%4.
     auto scores = [&](int kbuf, f32x16 (&s)[2]) {
         const POD_LDS unsigned char *kb = lds + kbuf * L::kTileBytes;
+        uint32_t k_base = k_rd0;
+        asm("" : "+v"(k_base));                   // opaque copy: the XORs below stay inside the loop
+        // Operation i = (key block i / KS, slice i % KS).  The LDS reads are written, and pinned,
+        // three operations ahead of the matrix instructions that use them: inlined into the fused
+        // kernel this block is otherwise emitted read-wait-multiply, sixteen times, and every
+        // matrix instruction waits a full LDS latency.  0x100 = LDS read, 0x008 = matrix op.
+        constexpr int kAhead = 3, kOps = 2 * KS;
+        auto k_frag = [&](int i) __attribute__((always_inline)) {
+            return *(const POD_LDS v8 *)(kb + (i / KS) * 32 * L::kRowBytes + (k_base ^ (uint32_t)((i % KS) << 5)));
+        };
+        v8 kk[kOps];
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
+        for (int i = 0; i < kAhead; ++i) kk[i] = k_frag(i);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[tb][r] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const v8 kk = *(const POD_LDS v8 *)(kb + tb * 32 * L::kRowBytes + k_rd[ks]);
-                s[tb] = N::mfma32(kk, q[ks], s[tb]);
-            }
+        for (int i = 0; i < kOps; ++i) {
+            if (i + kAhead < kOps) kk[i + kAhead] = k_frag(i + kAhead);
+            s[i / KS] = N::mfma32(kk[i], q[i % KS], s[i / KS]);
         }
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+        for (int i = 0; i < kOps - kAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     };
 
     if (n_tiles <= 0) return;                                // never planned; keeps the loop simple
@@ -552,19 +573,34 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                 for (int u = 0; u < 2; ++u) l_run = N::add_all(pk[tb][u], l_run);
             // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
             const POD_LDS unsigned char *vb = lds + (2 + cur) * L::kTileBytes;
+            uint32_t v_base = v_rd0;
+            asm("" : "+v"(v_base));               // as for K above
+            // Operation j = (channel block j / 4, key block (j / 2) % 2, half j % 2); its V fragment is
+            // two transposing reads.  As for K, the reads are written and pinned two operations
+            // ahead of the matrix instruction that uses them.
+            constexpr int kAheadV = 2, kOpsV = 4 * MB;
+            auto v_frag = [&](int j) __attribute__((always_inline)) {
+                const POD_LDS unsigned char *vp = vb + (((j >> 1) & 1) * 32 + 16 * (j & 1)) * L::kRowBytes +
+                                                  (v_base ^ (uint32_t)((j >> 2) << 6));
+                const s16x4 lo = lds_read_tr(vp);
+                const s16x4 hi = lds_read_tr(vp + 8 * L::kRowBytes);
+                return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+            };
+            v8 vv[kOpsV];
 #pragma unroll
-            for (int mb = 0; mb < MB; ++mb) {
+            for (int j = 0; j < kAheadV; ++j) vv[j] = v_frag(j);
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                    for (int u = 0; u < 2; ++u) {
-                        const POD_LDS unsigned char *vp = vb + (tb * 32 + 16 * u) * L::kRowBytes + v_rd[mb];
-                        const s16x4 lo = lds_read_tr(vp);
-                        const s16x4 hi = lds_read_tr(vp + 8 * L::kRowBytes);
-                        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        o[mb] = N::mfma32(__builtin_bit_cast(v8, both), pk[tb][u], o[mb]);
-                    }
+            for (int j = 0; j < kOpsV; ++j) {
+                if (j + kAheadV < kOpsV) vv[j + kAheadV] = v_frag(j + kAheadV);
+                o[j >> 2] = N::mfma32(vv[j], pk[(j >> 1) & 1][j & 1], o[j >> 2]);
             }
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAheadV, 0);
+#pragma unroll
+            for (int j = 0; j < kOpsV - kAheadV; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, kAheadV, 0);
         }
         wait_all_loads();                                    // K tile jt+2 and V tile jt+1 have landed
         __syncthreads();                                     // ... for every wavefront; tile jt is done
@@ -1080,12 +1116,24 @@ __device__ __forceinline__ int prefill_worker_run(const KernelArgs &a, unsigned 
             slot[1] = q | (tried << 8);
         }
         __syncthreads();
-        const int item = slot[0];
-        q = slot[1] & 255;
-        tried = slot[1] >> 8;
+        // The claimed index is the same for every thread, but it comes out of LDS: say so, and read
+        // the item through the constant address space, so that the item and everything derived
+        // from it (key range, tile bases, block ids) stays in scalar registers as in the
+        // stand-alone kernel.  Held in vector registers it cost the tile loop ~15 registers it
+        // needs to keep LDS reads ahead of the matrix instructions.
+        const int item = __builtin_amdgcn_readfirstlane(slot[0]);
+        const int packed = __builtin_amdgcn_readfirstlane(slot[1]);
+        q = packed & 255;
+        tried = packed >> 8;
         if (item < 0) break;
         const uint64_t tb = a.evlog ? wall_clock64() : 0;
-        prefill_item_run<DT, D, LAYOUT>(a, a.pitems[item], smem);
+        PrefillItem it;
+        {
+            const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.pitems + 8 * (int64_t)item;
+            it.req = w[0]; it.kv_head = w[1]; it.row0 = w[2]; it.n_rows = w[3];
+            it.kv_begin = w[4]; it.kv_end = w[5]; it.prow0 = w[6]; it.split = w[7];
+        }
+        prefill_item_run<DT, D, LAYOUT>(a, it, smem);
         if (a.evlog && threadIdx.x == 0) log_event(a, kPrefill, item, tb);
         ++n_done;
     }
@@ -1163,6 +1211,11 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     int n_first, n_second;
     uint64_t t_switch = 0;
     // A workgroup takes its decode seat when it enters the decode operation, first or second.
+    // There are n_dwgs seats, one per compute unit: the decode stream is fastest with four
+    // wavefronts per unit (more of them only queue up in the memory system and slow each other
+    // down unevenly), so a workgroup that finds every seat taken leaves the decode work to the
+    // seated ones.  Every workgroup asks for a seat sooner or later and the grid has at least
+    // n_dwgs workgroups, so all seats, and with them all fixed first units, are taken.
     auto take_seat = [&]() {
         __syncthreads();
         if (threadIdx.x == 0) bind[1] = (int)atomicAdd(&hdr->next_item[kDecode], 1u);
@@ -1174,10 +1227,10 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
         n_first = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
         if (a.trace) t_switch = wall_clock64();
         const int seat = take_seat();
-        n_second = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd);
+        n_second = seat < a.n_dwgs ? decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd) : 0;
     } else {
         const int seat = take_seat();
-        n_first = decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd);
+        n_first = seat < a.n_dwgs ? decode_worker_run<DT, D, LAYOUT>(a, smem, seat, xcd) : 0;
         if (a.trace) t_switch = wall_clock64();
         n_second = prefill_worker_run<DT, D, LAYOUT>(a, smem, &bind[4], xcd);
     }

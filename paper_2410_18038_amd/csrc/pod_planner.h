@@ -30,7 +30,7 @@ struct Plan {
     int pq_begin[kXcdQueues + 1] = {0};     // per-XCD prefill queues inside pitems
     int dq_begin[16] = {0};                 // per-XCD decode queues inside dunits (entries 0..8 used)
     int n_static_seats = 0;                 // decode seats whose first four units are fixed
-    int n_dwgs = 0;                         // workgroups of the stand-alone decode kernel
+    int n_dwgs = 0;                         // decode workers: workgroups of the stand-alone decode kernel, decode seats of the fused one
     int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)
     size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_dq = 0, off_part_o = 0, off_part_ml = 0;

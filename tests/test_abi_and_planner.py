@@ -139,8 +139,9 @@ def coverage_check(prm, meta):
     group = prm.n_q_heads // prm.n_kv_heads
     items, units = plan.prefill_items(), plan.decode_units()
     assert len(items) == info.n_prefill_items and len(units) == info.n_decode_units
-    # decode workers are persistent: at most two per compute unit, never more than a wave per unit
-    assert info.fused_grid == min(2 * info.n_compute_units, len(items) + (len(units) + 3) // 4)
+    # decode workers are persistent: at most one per compute unit, never more than a wave per unit
+    assert info.fused_grid == min(2 * info.n_compute_units,
+                                  len(items) + min(info.n_compute_units, (len(units) + 3) // 4))
     # prefill: per (request, kv head, row block) the key ranges tile [0, kmax) without gaps
     blocks = {}
     for req, kvh, row0, n_rows, k0, k1, prow0, split in items:
