@@ -315,23 +315,6 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     // workgroups it would fill at one wavefront per unit, up to one resident round.
     const int n_decode_ctas = std::min(2 * n_cus, ceil_div((int)plan.dunits.size(), kWavesPerWg));
     role_ratio(prm.policy, (int)plan.pitems.size(), n_decode_ctas, plan.p_ratio, plan.d_ratio);
-    // Automatic policy only: a batch whose prefill is far longer than its decode stream is bound by
-    // the matrix units and the power they draw, not by anything a decode workgroup could use in the
-    // meantime; running the two side by side then only slows the prefill items down (measured: 1470
-    // against 1410 us on a 2048-token chunk at 32K context with 32 decodes).  Such a batch keeps the
-    // single launch but every workgroup starts with prefill, and the decode seats are taken as the
-    // prefill items run out.  Rates are what this GPU sustains: ~1.0 PFLOP/s for the prefill items,
-    // ~6.5 TB/s for the decode stream.
-    if (prm.policy == POD_POLICY_AUTO && !plan.pitems.empty() && !plan.dunits.empty()) {
-        double flops = 0.0, bytes = 0.0;
-        for (int r = 0; r < prm.n_prefill; ++r) {
-            const double q = seq_meta[4 * r + 1], prefix = seq_meta[4 * r + 2] - seq_meta[4 * r + 1];
-            flops += 4.0 * prm.head_dim * prm.n_q_heads * (q * prefix + q * (q + 1) / 2);
-        }
-        for (int r = prm.n_prefill; r < n_req; ++r)
-            bytes += 4.0 * prm.head_dim * prm.n_kv_heads * seq_meta[4 * r + 2];
-        if (flops / 1.0e15 > 2.0 * (bytes / 6.5e12)) { plan.p_ratio = 1; plan.d_ratio = 0; }
-    }
     // The fused launch is one resident round of workgroups (two per compute unit) that loop over
     // work, or fewer when the batch is smaller than that.
     plan.fused_grid = std::min(2 * n_cus, (int)plan.pitems.size() + plan.n_dwgs);
