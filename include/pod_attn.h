@@ -67,7 +67,8 @@ typedef enum {
 
 /* Which operation a workgroup takes first on its compute unit (Section 4.1, the two policies). */
 typedef enum {
-    POD_POLICY_AUTO = 0,
+    POD_POLICY_AUTO = 0,        /* proportional, but never more decode than prefill workgroups at the
+                                   start: a compute unit seats one decode worker                      */
     POD_POLICY_ALTERNATE = 1,   /* 50:50 - successive workgroups of a unit alternate             */
     POD_POLICY_PROPORTIONAL = 2 /* in the ratio of prefill to decode work of this batch          */
 } pod_policy;
@@ -144,8 +145,9 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
 /*
  * Optional execution trace, the evidence for co-location (Section 4.1 wants both operations
  * resident on every multiprocessor).  `trace` is device memory of at least 48 bytes per workgroup
- * of the largest launch (n_prefill_items + decode workgroups of the stand-alone kernels, which is
- * never less than pod_attn_plan_info.fused_grid), or NULL to switch tracing off.  After a forward
+ * of the largest launch (the larger of pod_attn_plan_info.fused_grid and n_prefill_items plus the
+ * decode workgroups of the stand-alone kernel, of which there are at most n_compute_units and at
+ * most (n_decode_units + 3) / 4), or NULL to switch tracing off.  After a forward
  * call, record w of the fused launch holds int32 {hardware unit id, first operation (0 prefill /
  * 1 decode), work items done in the first operation, work items done after switching} followed by
  * three uint64 device timestamps (100 MHz): begin, switch of operation, end, and 8 bytes of

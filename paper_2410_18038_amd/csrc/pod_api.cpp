@@ -170,7 +170,9 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
 pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trace_bytes)
 {
     if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
-    const size_t need = (plan->p.pitems.size() + (size_t)plan->p.n_dwgs) * sizeof(pod::TraceRecord);   // serial mode: one record per workgroup of either kernel
+    // one record per workgroup of the largest launch: the two stand-alone kernels together, or the fused round
+    const size_t n_records = std::max(plan->p.pitems.size() + (size_t)plan->p.n_dwgs, (size_t)plan->p.fused_grid);
+    const size_t need = n_records * sizeof(pod::TraceRecord);
     if (trace && trace_bytes < need) return fail(POD_ERR_WORKSPACE, "trace buffer too small");
     plan->p.trace = trace;
     plan->p.trace_bytes = trace ? trace_bytes : 0;

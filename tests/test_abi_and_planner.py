@@ -140,8 +140,10 @@ def coverage_check(prm, meta):
     items, units = plan.prefill_items(), plan.decode_units()
     assert len(items) == info.n_prefill_items and len(units) == info.n_decode_units
     # decode workers are persistent: at most one per compute unit, never more than a wave per unit
-    assert info.fused_grid == min(2 * info.n_compute_units,
-                                  len(items) + min(info.n_compute_units, (len(units) + 3) // 4))
+    n_workers = min(info.n_compute_units, (len(units) + 3) // 4)
+    full_round = n_workers == info.n_compute_units and len(items) > 0
+    assert info.fused_grid == (2 * info.n_compute_units if full_round
+                               else min(2 * info.n_compute_units, len(items) + n_workers))
     # prefill: per (request, kv head, row block) the key ranges tile [0, kmax) without gaps
     blocks = {}
     for req, kvh, row0, n_rows, k0, k1, prow0, split in items:
@@ -314,10 +316,17 @@ def test_proportional_policy_reproduces_the_papers_example():
                           block_size=0)
     prm.decode_chunk = 256
     prm.prefill_split_len = 1 << 20          # one item per row block
+    prm.policy = pod.POLICY_PROPORTIONAL
     plan = pod.pod_attn_plan_create(prm, meta)
     info = plan.info()
     assert (info.n_prefill_items, (info.n_decode_units + 3) // 4) == (n_p, n_d)
     assert (info.prefill_ratio, info.decode_ratio) == (1, 2)
+    plan.close()
+    # the automatic policy never starts more decode than prefill workgroups on a unit (a unit seats
+    # one decode worker), but follows the proportion when prefill is the larger side
+    prm.policy = pod.POLICY_AUTO
+    plan = pod.pod_attn_plan_create(prm, meta)
+    assert (plan.info().prefill_ratio, plan.info().decode_ratio) == (1, 1)
     plan.close()
     # all arrivals on one compute unit, nobody leaves: roles must follow the printed pattern
     served, roles, items = pod.pod_attn_simulate_binder(n_p, n_d, 1, 2, np.zeros(12, dtype=np.int32))
