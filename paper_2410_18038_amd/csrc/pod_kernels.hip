@@ -294,8 +294,8 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // readers: byte offsets inside a tile, without the compile-time row blocks.  The swizzles are
     // XORs of the chunk index, so slice ks of K sits at k_rd0 ^ (ks << 5) and block mb of V at
     // v_rd0 ^ (mb << 6): one register each, and one XOR with a constant at the point of use
-    // (eight registers fewer than a table of addresses, which this loop needs for its LDS reads
-    // in flight).
+    // (ten registers fewer than a table of addresses at D = 128, which this loop needs for its
+    // LDS reads in flight).
     const uint32_t k_rd0 = (uint32_t)(n32 * L::kRowBytes + k_swizzle<D>(n32, h) * 16);
     uint32_t v_rd0;
     {
@@ -671,13 +671,13 @@ template <int D> struct DecodeLds {
 };
 
 template <int D, int LAYOUT> struct DecodeRing {
-    // A slot holds the K and V rows of 16 keys: D / 4 registers, 8 KB at D = 128.  With every
-    // wavefront slot of the chip streaming, one slot in flight per wavefront (16 MB chip-wide) is
-    // what keeps HBM busy; deeper rings only lengthen the queues in the memory system, which
-    // measured slower for the decode role itself (6.1 -> 6.3 TB/s going from 5 slots to 2 on 64
-    // requests x 32 heads x 4096 keys) and for the prefill role running beside it (its tile loads
-    // wait in the same queues).  The price: a wavefront alone on the chip streams 10.7 instead
-    // of 12.8 GB/s.  The any-block-size layout looks up block ids with vector loads before each
+    // A slot holds the K and V rows of 16 keys: D / 4 registers, 8 KB at D = 128.  One slot in
+    // flight per streaming wavefront while the other is computed keeps HBM busy; deeper rings only
+    // lengthen the queues in the memory system, which measured slower for the decode role itself
+    // (6.1 -> 6.3 TB/s going from 5 slots to 2 on 64 requests x 32 heads x 4096 keys with eight
+    // streaming wavefronts per unit; with the four there are now, 2, 3 and 4 slots measure the
+    // same) and for the prefill role running beside it (its tile loads wait in the same queues).
+    // The price: a wavefront alone on the chip streams 10.7 instead of 12.8 GB/s.  The any-block-size layout looks up block ids with vector loads before each
     // step and gets one more slot to cover them; D = 64 slots are half the size.
     static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 3 : 2) : 4;
 };
