@@ -36,23 +36,33 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def bind(path: str):
+    """Load a compiled oracle (this one, or a deliberately broken copy a test has built) and
+    declare its entry points."""
+    lib = ctypes.CDLL(path)
+    _declare(lib)
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        u16p = ctypes.POINTER(ctypes.c_uint16)
-        i32p = ctypes.POINTER(ctypes.c_int32)
-        lib.pod_oracle_attention.restype = ctypes.c_int
-        lib.pod_oracle_attention.argtypes = [
-            u16p, u16p, u16p, u16p, i32p, i32p,
-            ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-            ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
-            i32p, ctypes.c_int64, ctypes.POINTER(ctypes.c_double)]
-        lib.pod_oracle_widen.restype = ctypes.c_double
-        lib.pod_oracle_widen.argtypes = [ctypes.c_int, ctypes.c_uint16]
-        lib.pod_oracle_num_threads.restype = ctypes.c_int
-        _lib = lib
+        _lib = bind(build())
     return _lib
+
+
+def _declare(lib):
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.pod_oracle_attention.restype = ctypes.c_int
+    lib.pod_oracle_attention.argtypes = [
+        u16p, u16p, u16p, u16p, i32p, i32p,
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_double, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+        i32p, ctypes.c_int64, ctypes.POINTER(ctypes.c_double)]
+    lib.pod_oracle_widen.restype = ctypes.c_double
+    lib.pod_oracle_widen.argtypes = [ctypes.c_int, ctypes.c_uint16]
+    lib.pod_oracle_num_threads.restype = ctypes.c_int
 
 
 def num_threads() -> int:
