@@ -18,20 +18,26 @@ constexpr int kThreads = 256;
 constexpr int kUnroll = 8;
 
 // Every lane reads 16 bytes per load, a wavefront 1 KiB of consecutive memory; kUnroll loads are
-// in flight per lane.  The xor keeps the loads alive; the store never happens for real data.
+// in flight per lane; every workgroup walks a contiguous region of its own.  Of the patterns tried
+// (grid-stride, one region per workgroup, one region per wavefront; 256 to 1024 threads; one to
+// eight workgroups per compute unit; with and without the non-temporal hint) this one, with two
+// workgroups of 256 threads per unit, read fastest on MI355X: 7.2-7.3 TB/s against 6.2-6.3 for a
+// grid-stride loop with eight workgroups per unit.  The xor keeps the loads alive; the store never
+// happens for real data.
 __global__ __launch_bounds__(kThreads) void hbm_read_kernel(const u32x4 *src, size_t n_vec, uint32_t *sink)
 {
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const size_t per = (n_vec + gridDim.x - 1) / gridDim.x;
+    const size_t end = per * (blockIdx.x + 1) < n_vec ? per * (blockIdx.x + 1) : n_vec;
+    size_t i = per * blockIdx.x + threadIdx.x;
     u32x4 acc = {0u, 0u, 0u, 0u};
-    for (; i + (kUnroll - 1) * stride < n_vec; i += kUnroll * stride) {
+    for (; i + (kUnroll - 1) * kThreads < end; i += kUnroll * kThreads) {
         u32x4 v[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+        for (int u = 0; u < kUnroll; ++u) v[u] = __builtin_nontemporal_load(src + i + u * kThreads);
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) acc ^= v[u];
     }
-    for (; i < n_vec; i += stride) acc ^= src[i];
+    for (; i < end; i += kThreads) acc ^= src[i];
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) sink[0] = acc.x;
 }
 
@@ -151,7 +157,7 @@ pod_status pod_attn_probe_hbm_read(const void *buf, size_t bytes, void *sink, vo
     int dev = 0, cus = 256;
     if (hipGetDevice(&dev) != hipSuccess) return POD_ERR_HIP;
     (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    hbm_read_kernel<<<dim3(cus * 8), dim3(kThreads), 0, (hipStream_t)stream>>>(
+    hbm_read_kernel<<<dim3(cus * 2), dim3(kThreads), 0, (hipStream_t)stream>>>(
         (const u32x4 *)buf, bytes / 16, (uint32_t *)sink);
     return hipGetLastError() == hipSuccess ? POD_OK : POD_ERR_HIP;
 }
