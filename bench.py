@@ -110,10 +110,16 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         f"(KV cache {2 * batch.k_cache.numel() * 2 / 2**30:.2f} GiB)")
     attn = pod.HybridAttention(batch)
     info = attn.info
+    # The baselines get the plan that suits them: their stand-alone prefill kernel has both slots
+    # of every compute unit to itself, so its items may fill two rounds (the fused launch plans one
+    # round when a decode worker holds the other slot of every unit).
+    attn_base = pod.HybridAttention(batch, max_prefill_waves=2)
     out = torch.empty((batch.n_rows, batch.n_q_heads, batch.head_dim), dtype=batch.torch_dtype, device=dev)
+    baseline_modes = (pod.MODE_SERIAL, pod.MODE_STREAMS, pod.MODE_PREFILL_ONLY)
 
     def fwd(mode):
-        return lambda: attn.forward(batch, out=out, mode=mode)
+        which = attn_base if (mode & 0xff) in baseline_modes else attn
+        return lambda: which.forward(batch, out=out, mode=mode)
 
     flops = batch.prefill_flops()
     kv_bytes = batch.kv_bytes()
@@ -228,6 +234,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         rec["overlap_roofline_measured_peaks_us"] = t_roof_meas
         rec["pct_of_overlap_roofline_measured_peaks"] = 100.0 * t_roof_meas / results[main_mode]["median_us"]
     attn.close()
+    attn_base.close()
     return rec
 
 
@@ -296,7 +303,7 @@ def run_chunk_series(model, n_decode, steps, warmup, torch, pod, wl):
     for k in range(n_chunks):
         batch = wl.series_chunk(base, k)
         rec = {"chunk": k, "kv_len": int(batch.seq_meta[0, 2])}
-        variants = {"fused": {}, "serial": {}, "streams": {},
+        variants = {"fused": {}, "serial": {"max_prefill_waves": 2}, "streams": {"max_prefill_waves": 2},
                     "fused_alternate": {"policy": pod.POLICY_ALTERNATE},
                     "fused_uncapped": {"max_prefill_waves": 64}}
         plans = {}

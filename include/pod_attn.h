@@ -95,7 +95,8 @@ typedef struct {
     int64_t kv_seq_stride;      /* contiguous: elements between sequences (>= max kv_len*Hkv*d)  */
     int32_t policy;             /* pod_policy                                                    */
     int32_t max_prefill_waves;  /* cap on prefill split-KV (Section 4.2.4): prefill work items
-                                   fill at most this many chip-wide rounds; 0 = 2                */
+                                   fill at most this many chip-wide rounds; 0 = automatic: 2, or
+                                   1 when the decode work puts a worker on every compute unit    */
     int32_t decode_chunk;       /* tokens per decode work unit (split-KV length); 0 = automatic  */
     int32_t prefill_split_len;  /* minimum keys per prefill split; 0 = automatic                 */
     int32_t n_compute_units;    /* 0 = ask the current device (256 on MI355X if none is present) */

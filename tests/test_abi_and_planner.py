@@ -234,18 +234,28 @@ def test_plan_covers_small_benchmark_batches(config, index):
 
 
 def test_plan_shapes_for_the_large_configs():
-    # config 2: 32 heads x 8 row blocks = 256 items, no split (256 items already fill 256 units once,
-    # and two rounds allow 512 -> 2 splits of >= 1024 keys)
+    # config 2: 32 heads x 8 row blocks = 256 items.  With a decode worker on every unit the items fill
+    # the other slots once: no split; asked for two rounds, 512 items in 2 splits of >= 1024 keys
     prm, meta = meta_only("c2", [(1024, 4096)], [4096] * 64, hq=32, hkv=32, block_size=0)
     info = coverage_check(prm, meta)
-    assert info.n_prefill_items in (256, 512) and info.max_prefill_splits <= 2
+    assert info.n_prefill_items == 256 and info.max_prefill_splits == 1
     assert info.n_decode_units == 64 * 32 * info.max_decode_splits
+    prm.max_prefill_waves = 2
+    info = coverage_check(prm, meta)
+    assert info.n_prefill_items == 512 and info.max_prefill_splits == 2
+    # the same chunk with little decode work beside it: two rounds by default
+    prm, meta = meta_only("c2-few", [(1024, 4096)], [4096] * 2, hq=32, hkv=32, block_size=0)
+    info = coverage_check(prm, meta)
+    assert info.n_prefill_items == 512 and info.max_prefill_splits == 2
     # config 4: 4 kv heads x 128 row blocks = 512 items = two rounds -> no split (Section 4.2.4)
     prm, meta = meta_only("c4", [(2048, 32768)], [32768] * 32, hq=32, hkv=4)
     info = coverage_check(prm, meta)
     assert info.n_prefill_items == 512 and info.max_prefill_splits == 1
-    # config 3: 128 row blocks -> splits allowed up to 4 (512 items)
+    # config 3: 128 row blocks -> 2 splits (256 items) beside its decodes, 4 (512 items) in two rounds
     prm, meta = meta_only("c3", [(512, 8192)], [9000] * 128, hq=32, hkv=8)
+    info = coverage_check(prm, meta)
+    assert info.max_prefill_splits == 2 and info.n_prefill_items <= 256
+    prm.max_prefill_waves = 2
     info = coverage_check(prm, meta)
     assert info.max_prefill_splits == 4 and info.n_prefill_items <= 512
 
