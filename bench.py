@@ -29,8 +29,8 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
-    (2, 0): 4509431706,     # 2178738.4 KiB fetched, 46265.1 KiB written
-    (4, 0): 2591117722,     # 1245176.9 KiB fetched, 40034.6 KiB written
+    (2, 0): 4406250906,     # 2140618.5 KiB fetched, 21742.4 KiB written
+    (4, 0): 2595136410,     # 1247175.0 KiB fetched, 39962.9 KiB written
 }
 
 
