@@ -101,6 +101,26 @@ def measure_peaks(torch, pod):
     return {"hbm_read_GBps": (4 << 30) / t_rd / 1e3, "mfma_f16_TFLOPs": flops[0] / t_mf / 1e6}
 
 
+def plan_times_us(attn, torch, pod, reps=5):
+    """Host time of the two calls made once per batch (every layer's forward reuses their result):
+    building the plan, and copying its tables into a workspace (ends with a stream synchronisation)."""
+    scratch = torch.empty(attn.ws_bytes + 256, dtype=torch.uint8, device=attn.workspace.device)
+    ws = (scratch.data_ptr() + 255) & ~255
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+    create, upload = [], []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        plan = pod.pod_attn_plan_create(attn.params, attn.batch_meta)
+        t1 = time.perf_counter()
+        pod.pod_attn_plan_upload(plan, ws, attn.ws_bytes, stream)
+        t2 = time.perf_counter()
+        plan.close()
+        create.append((t1 - t0) * 1e6)
+        upload.append((t2 - t1) * 1e6)
+    return {"create_us": float(np.median(create)), "upload_us": float(np.median(upload))}
+
+
 def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, pod, wl, peaks=None):
     dev = "cuda:0"
     t0 = time.time()
@@ -199,6 +219,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     kernel_us = float(np.mean(event_times_us(f_kernel, steps, torch)))
     attn.forward(batch, out=out, mode=pod.MODES[main_mode])       # leave `out` complete again
     torch.cuda.synchronize()
+    plan_us = plan_times_us(attn, torch, pod)
 
     bound = "hbm" if t_b >= t_f else "mfma"
     if bound == "hbm":
@@ -227,6 +248,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         "speedup_vs_serial": results["serial"]["median_us"] / results["fused"]["median_us"],
         "speedup_vs_streams": results["streams"]["median_us"] / results["fused"]["median_us"],
         "modes": results, "max_abs_err_vs_oracle": max_err, "cpu_baseline": cpu,
+        "plan_host_us": plan_us,       # once per batch, reused by every layer; not part of `value`
     }
     if peaks:
         t_roof_meas = max(flops / (peaks["mfma_f16_TFLOPs"] * 1e12), kv_bytes / (peaks["hbm_read_GBps"] * 1e9)) * 1e6
