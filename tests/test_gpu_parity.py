@@ -286,6 +286,29 @@ def test_full_size_batches_on_sampled_rows(config, index):
     attn.close()
 
 
+@pytest.mark.parametrize("dtype,block_size", [(wl.F16, 0), (wl.BF16, 16)])
+def test_contexts_of_128k_tokens(dtype, block_size):
+    """Contexts far beyond the benchmark's (128K keys, and lengths that are no multiple of anything):
+    offsets, unit counts and split counts at the large end.  Sampled rows, every head of each."""
+    batch = wl.make_batch("ctx128k", prefill=[(96, 131072)], decode_kv_lens=[131072, 100003, 65537],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=dtype, block_size=block_size,
+                          seed=77, device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    out = attn.forward(batch)
+    torch.cuda.synchronize()
+    rows = _sample_rows(batch, 6, 3, seed=5)
+    print(f"case {batch.name}: {len(rows)} sampled rows of {batch.n_rows}, {attn.info.n_decode_units} units, "
+          f"{attn.info.n_prefill_items} items", flush=True)
+    want = oracle_out(batch, rows=rows)
+    got = out[torch.from_numpy(rows.astype(np.int64)).to("cuda:0")].to(torch.float64).cpu().numpy()
+    assert bool(torch.isfinite(out.to(torch.float32)).all())
+    err = np.abs(got - want).max()
+    assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} on sampled rows of {batch.name}"
+    serial = attn.forward(batch, mode=pod.MODE_SERIAL)
+    assert torch.equal(out.view(torch.int16), serial.view(torch.int16))
+    attn.close()
+
+
 @pytest.mark.parametrize("model,n_decode,chunk", [("yi-6b", 54, 0), ("yi-6b", 55, 31), ("llama-3-8b", 64, 15)])
 def test_chunk_series_batches_on_sampled_rows(model, n_decode, chunk):
     """Chunks of a 16K prompt next to decodes at 16K context (the shape of the paper's Figure 6 and
