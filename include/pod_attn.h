@@ -210,7 +210,9 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  * POD_MODE_FLAG_NO_COMBINE.
  * The call only launches kernels on `stream` (no allocation, no memset, no wait on the host), so
  * in the FUSED, SERIAL and single-operation modes it may be recorded into a HIP graph; the
- * STREAMS mode creates its two side streams and events on first use and is not meant for capture.
+ * STREAMS mode creates its two side streams and events on first use (they belong to the plan and are
+ * destroyed with it; that first call must not run beside another call on the same plan from a second
+ * host thread) and is not meant for capture.
  * Two forward calls that use the same workspace must not overlap in time.
  */
 pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
