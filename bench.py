@@ -30,6 +30,7 @@ MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
     (2, 0): 4406250906,     # 2140618.5 KiB fetched, 21742.4 KiB written
+    (3, 0): 4993570816,     # 2417705.6 KiB fetched, 41122.8 KiB written
     (4, 0): 2595136410,     # 1247175.0 KiB fetched, 39962.9 KiB written
 }
 
