@@ -223,27 +223,40 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
                             int32_t mode, void *stream);
 
 /*
- * Host model of the on-device role binder (Section 4.1, the scheduling listing), for tests.
- * `events` (host, n_events entries) is a history of one launch: a value v >= 0 means a workgroup
- * arrives on compute unit v (any id; taken modulo 1024); a value v < 0 means the workgroup
- * created by arrival number -v - 1 (counting arrivals from 0) has finished and leaves its unit.
- * Each arrival takes a ticket from its unit's counter, picks prefill or decode so that the
- * unit's resident mix stays near prefill_ratio : decode_ratio (a tie is broken by the listing's
- * rule, ticket mod (p + d) < p means prefill, where unit u counts its tickets from 2 * u so that a
- * pattern longer than the two workgroups a unit holds is spread over the units), claims the next
- * work id of that operation and
- * switches operation if that one is exhausted.  For arrival number a, role_out[a] is 0 (prefill),
- * 1 (decode) or -1 (nothing left) and item_out[a] the claimed id (-1 if none); both arrays hold
- * one entry per arrival.  Returns the number of arrivals that got work, or -1 for bad arguments.
- * The fused kernel picks the first operation of every resident workgroup with this same rule
- * (the same code); on the device a workgroup then stays: it keeps claiming work of its operation
- * and switches once when that runs out (the persistent variant of Section 4.4), so one device
- * workgroup stands for a run of arrivals of this model.
+ * The role rule of the on-device binder (Section 4.1, the scheduling listing), host-callable for
+ * tests: the first operation of the workgroup that holds `ticket` (arrivals on its hardware unit
+ * before it, counted from 0) on unit `unit`: 0 prefill when (ticket + 2 * unit) mod (p + d) < p,
+ * else 1 decode.  Unit u counts from 2u because a unit holds two workgroups of the fused kernel at
+ * a time, so that a pattern longer than two is spread over the units; with all arrivals on unit 0
+ * this is the listing's own rule (Section 5.4.2: 50 prefill and 100 decode CTAs run P, D, D, ...).
+ * The fused kernel calls the same code.  Returns -1 for bad arguments.
  */
-int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items,
-                                 int32_t prefill_ratio, int32_t decode_ratio,
-                                 const int32_t *events, int32_t n_events,
-                                 int32_t *role_out, int32_t *item_out);
+int32_t pod_attn_role_for_ticket(int32_t ticket, int32_t prefill_ratio, int32_t decode_ratio, int32_t unit);
+
+/*
+ * Host model of one fused launch, for tests: what the workgroups do between landing on a compute
+ * unit and leaving it (Section 4.1: the scheme must hold however the hardware places and times
+ * the workgroups; Section 4.4: persistent workgroups that loop over work).  No GPU is used.
+ *   unit_of_wg[w]  hardware unit id (xcc << 6 | se << 4 | cu, < 1024) workgroup w lands on
+ *   order[k]       actor whose next step runs at time k.  Actor 4w is workgroup w's leader, whose
+ *                  steps are: take the unit's ticket and pick the first operation; as a prefill
+ *                  worker, one claim on the prefill queue it is at (its XCD's queue first, then the
+ *                  others; a used-up queue moves it on, after all eight the operation is done); as
+ *                  a decode worker, take a seat (workers beyond the plan's seats skip the
+ *                  operation).  Actors 4w .. 4w+3 are its wavefronts while it is a decode worker:
+ *                  the fixed first unit 4 * seat + v of the first seats without a claim, then one
+ *                  claim per step on the decode queue the wavefront is at (same walk over the eight
+ *                  queues).  A workgroup switches operation once and then ends.  Entries naming an
+ *                  actor that has nothing to do at that moment are skipped; when `order` is used
+ *                  up, all unfinished actors run on in turn until the launch has drained.
+ * Outputs (host, each may be NULL): first_role[w] 0 prefill / 1 decode; seat_of_wg[w] (untouched if
+ * w never asked); item_owner[i] = workgroup that ran prefill item i; unit_owner[u] = actor that ran
+ * decode unit u (-1 = nobody).  Returns the number of steps executed, -1 for bad arguments, -2 if
+ * any work id was handed out twice.
+ */
+int32_t pod_attn_simulate_launch(const pod_attn_plan *plan, const int32_t *unit_of_wg, int32_t n_wgs,
+                                 const int32_t *order, int32_t n_order, int32_t *first_role,
+                                 int32_t *seat_of_wg, int32_t *item_owner, int32_t *unit_owner);
 
 /*
  * Read one row of the plan's work tables (host), for tests:
@@ -280,7 +293,7 @@ pod_status pod_attn_probe_hbm_read(const void *buf, size_t bytes, void *sink, vo
 pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, void *stream);
 
 /*
- * The co-location experiment of Section 3.2 (Figure 7), independent of attention: a compute-bound
+ * The co-location experiment of Section 3.3 (Figure 7), independent of attention: a compute-bound
  * operation (n_compute_items workgroups' worth of multiply-add loops, compute_iters rounds each)
  * and a memory-bound one (c = a + b over n_memory_items chunks of bytes_per_item bytes per array),
  * launched as

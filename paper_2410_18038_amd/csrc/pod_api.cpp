@@ -344,49 +344,141 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     return POD_OK;
 }
 
-int32_t pod_attn_simulate_binder(int32_t n_prefill_items, int32_t n_decode_items,
-                                 int32_t prefill_ratio, int32_t decode_ratio,
-                                 const int32_t *events, int32_t n_events,
-                                 int32_t *role_out, int32_t *item_out)
+int32_t pod_attn_role_for_ticket(int32_t ticket, int32_t prefill_ratio, int32_t decode_ratio, int32_t unit)
 {
-    if (n_events < 0 || (n_events > 0 && (!events || !role_out || !item_out))) return -1;
-    if (prefill_ratio < 0 || decode_ratio < 0 || prefill_ratio + decode_ratio <= 0) return -1;
-    std::vector<uint32_t> cu_state(pod::kCuSlots, 0u);
-    uint32_t next_item[2] = {0u, 0u};
-    const uint32_t limit[2] = {(uint32_t)std::max(n_prefill_items, 0), (uint32_t)std::max(n_decode_items, 0)};
-    std::vector<int> arrival_cu, arrival_role;
-    int32_t served = 0, n_out = 0;
-    for (int32_t ev = 0; ev < n_events; ++ev) {
-        const int32_t v = events[ev];
-        if (v < 0) {                                 // departure of arrival number -v - 1
-            const size_t who = (size_t)(-(int64_t)v - 1);
-            if (who >= arrival_cu.size() || arrival_role[who] == pod::kNone) continue;
-            cu_state[(size_t)arrival_cu[who]] -=
-                arrival_role[who] == pod::kPrefill ? pod::kRunPrefillOne : pod::kRunDecodeOne;
-            arrival_role[who] = pod::kNone;
-            continue;
+    if (ticket < 0 || unit < 0 || prefill_ratio < 0 || decode_ratio < 0 || prefill_ratio + decode_ratio <= 0) return -1;
+    return pod::role_for_ticket((uint32_t)ticket, prefill_ratio, decode_ratio, unit);
+}
+
+// Host model of the fused launch.  Every actor is a small state machine whose steps are the
+// atomic operations the device code performs, in the device's order; `order` decides whose step
+// comes next, which stands for every timing the hardware could produce.
+int32_t pod_attn_simulate_launch(const pod_attn_plan *plan, const int32_t *unit_of_wg, int32_t n_wgs,
+                                 const int32_t *order, int32_t n_order, int32_t *first_role,
+                                 int32_t *seat_of_wg, int32_t *item_owner, int32_t *unit_owner)
+{
+    if (!plan || n_wgs < 0 || n_order < 0 || (n_wgs > 0 && !unit_of_wg) || (n_order > 0 && !order)) return -1;
+    const pod::Plan &p = plan->p;
+    const int n_items = (int)p.pitems.size(), n_units = (int)p.dunits.size();
+    for (int i = 0; i < n_items && item_owner; ++i) item_owner[i] = -1;
+    for (int i = 0; i < n_units && unit_owner; ++i) unit_owner[i] = -1;
+    constexpr int W = pod::kWavesPerWg, Q = pod::kXcdQueues;
+
+    // the counters of the workspace header
+    std::vector<uint32_t> cu_ticket(pod::kCuSlots, 0u);
+    uint32_t next_seat = 0, next_pitem[Q] = {0}, next_dunit[Q] = {0};
+
+    enum Phase { kBind, kPrefillClaims, kSeat, kDecodeWaves, kEnd };
+    struct Wave { int cq = 0, tried = 0; bool started = false, done = false; };
+    struct Wg {
+        Phase phase = kBind;
+        int first = pod::kNone, roles_done = 0, xcd = 0, seat = -1;
+        int pq = 0, ptried = 0;                // prefill queue cursor (kept across the role switch, as on the device)
+        Wave wave[W];
+    };
+    std::vector<Wg> wgs((size_t)n_wgs);
+    int32_t owner_errors = 0;
+
+    auto next_phase = [&](Wg &g) {
+        // after a role has run dry: the other role, then the end
+        ++g.roles_done;
+        if (g.roles_done >= 2) { g.phase = kEnd; return; }
+        const int next_role = g.first == pod::kPrefill ? pod::kDecode : pod::kPrefill;
+        g.phase = next_role == pod::kPrefill ? kPrefillClaims : kSeat;
+    };
+    auto start_role = [&](Wg &g, int role) { g.phase = role == pod::kPrefill ? kPrefillClaims : kSeat; };
+    auto wg_finished = [&](const Wg &g) { return g.phase == kEnd; };
+
+    // One step of workgroup w's leader (actor 4w) or of its wavefront v (actor 4w + v) while the
+    // workgroup is a decode worker.  Returns false when that actor has nothing to do right now.
+    auto step = [&](int actor) -> bool {
+        const int w = actor / W, v = actor % W;
+        if (w < 0 || w >= n_wgs) return false;
+        Wg &g = wgs[(size_t)w];
+        switch (g.phase) {
+        case kBind: {
+            if (v != 0) return false;
+            const unsigned cu = (unsigned)unit_of_wg[w] & (pod::kCuSlots - 1);
+            const uint32_t ticket = cu_ticket[cu]++;
+            g.first = pod::role_for_ticket(ticket, p.p_ratio, p.d_ratio, (int)cu);
+            g.xcd = (int)(cu >> 6);
+            g.pq = g.xcd & (Q - 1);
+            if (first_role) first_role[w] = g.first;
+            start_role(g, g.first);
+            return true;
         }
-        const unsigned cu = (unsigned)v & (pod::kCuSlots - 1);
-        const uint32_t state = cu_state[cu];
-        cu_state[cu] += pod::kTicketOne;
-        int role = pod::role_for_arrival(state, prefill_ratio, decode_ratio, (int)cu);
-        uint32_t id = next_item[role]++;
-        if (id >= limit[role]) {
-            role ^= 1;
-            id = next_item[role]++;
-            if (id >= limit[role]) role = pod::kNone;
+        case kPrefillClaims: {
+            if (v != 0) return false;
+            // one claim: the queue's counter is only touched while the queue is not known to be empty
+            if (g.ptried >= Q) { next_phase(g); return true; }
+            const int len = p.pq_begin[g.pq + 1] - p.pq_begin[g.pq];
+            const int k = len > 0 ? (int)next_pitem[g.pq]++ : len;
+            if (k < len) {
+                const int item = p.pq_begin[g.pq] + k;
+                if (item_owner) { if (item_owner[item] != -1) ++owner_errors; item_owner[item] = w; }
+            } else {
+                g.pq = (g.pq + 1) & (Q - 1);
+                ++g.ptried;
+            }
+            return true;
         }
-        if (role != pod::kNone) {
-            cu_state[cu] += role == pod::kPrefill ? pod::kRunPrefillOne : pod::kRunDecodeOne;
-            ++served;
+        case kSeat: {
+            if (v != 0) return false;
+            g.seat = (int)next_seat++;
+            if (seat_of_wg) seat_of_wg[w] = g.seat;
+            if (g.seat < p.n_dwgs) {
+                g.phase = kDecodeWaves;
+                for (Wave &x : g.wave) { x = Wave(); x.cq = g.xcd & (Q - 1); }
+            } else {
+                next_phase(g);                  // every seat is taken: the seated workers stream the decode work
+            }
+            return true;
         }
-        role_out[n_out] = role;
-        item_out[n_out] = role == pod::kNone ? -1 : (int32_t)id;
-        ++n_out;
-        arrival_cu.push_back((int)cu);
-        arrival_role.push_back(role);
+        case kDecodeWaves: {
+            Wave &x = g.wave[v];
+            if (x.done) return false;
+            auto own = [&](int unit) { if (unit_owner) { if (unit_owner[unit] != -1) ++owner_errors; unit_owner[unit] = actor; } };
+            if (!x.started && g.seat < p.n_static_seats) {
+                x.started = true;
+                own(g.seat * W + v);            // the fixed first unit: no claim
+            } else {
+                x.started = true;
+                // one claim on the queue the wavefront is at; a used-up queue sends it to the next
+                // non-empty one, and after all eight it is done
+                const int q0 = p.dq_begin[x.cq], q1 = p.dq_begin[x.cq + 1];
+                const int k = (int)next_dunit[x.cq]++;
+                if (k < q1 - q0) own(q0 + k);
+                else {
+                    do {
+                        x.cq = (x.cq + 1) & (Q - 1);
+                        ++x.tried;
+                    } while (x.tried < Q && p.dq_begin[x.cq + 1] == p.dq_begin[x.cq]);
+                    if (x.tried >= Q) x.done = true;
+                }
+            }
+            bool all = true;
+            for (const Wave &y : g.wave) all = all && y.done;
+            if (all) next_phase(g);
+            return true;
+        }
+        default:
+            return false;
+        }
+    };
+
+    int32_t steps = 0;
+    for (int32_t i = 0; i < n_order; ++i)
+        if (step(order[i])) ++steps;
+    // whoever is not finished yet runs on, round-robin, until the launch has drained
+    for (bool progress = true; progress;) {
+        progress = false;
+        for (int w = 0; w < n_wgs; ++w) {
+            if (wg_finished(wgs[(size_t)w])) continue;
+            for (int v = 0; v < W; ++v)
+                if (step(w * W + v)) { ++steps; progress = true; }
+        }
     }
-    return served;
+    return owner_errors ? -2 : steps;
 }
 
 }  // extern "C"

@@ -61,10 +61,10 @@ struct CombineEntry {
 // Counters at the head of the device workspace.  All zero between launches: the last
 // workgroup of a fused launch clears them.
 struct WsHeader {
-    // Per compute unit: bits 0-9 resident prefill workgroups, bits 10-19 resident decode
-    // workgroups, bits 20-31 arrivals so far (the ticket of Section 4.1's listing).
+    // Per compute unit: workgroups that have arrived on it so far in this launch (the ticket of
+    // Section 4.1's listing).
     uint32_t cu_state[kCuSlots];
-    uint32_t next_item[2];                 // next prefill item id; next decode worker id
+    uint32_t next_item[2];                 // [kDecode]: next decode seat
     uint32_t done;                         // workgroups that have finished
     uint32_t pad0;
     uint32_t next_pitem_xcd[kXcdQueues];   // next prefill item of each per-XCD queue (offset inside the queue)
@@ -77,28 +77,18 @@ struct WsHeader {
     uint32_t null_claim[kNullClaimLines][32];
 };
 
-constexpr uint32_t kRunPrefillOne = 1u;
-constexpr uint32_t kRunDecodeOne = 1u << 10;
-constexpr uint32_t kTicketOne = 1u << 20;
-
-// Which operation an arriving workgroup should start, given the snapshot of its unit's state.
-// Keeps resident prefill : decode workgroups near p : d; a tie falls back to the ticket rule
-// of Section 4.1 (ticket mod (p + d) < p means prefill).  A unit holds only kSlotsPerUnit
+// Which operation the workgroup holding `ticket` on hardware unit `unit` starts with: the ticket
+// rule of Section 4.1 (ticket mod (p + d) < p means prefill).  A unit holds only kSlotsPerUnit
 // workgroups at a time, so its own tickets would never get past the first entries of a longer
-// pattern; unit u therefore starts its tickets at kSlotsPerUnit * u, which spreads the pattern
-// over the chip (4:1 puts a decode workgroup on every fifth slot; 1:1 still gives every unit one
-// of each).  The fused kernel calls this with the resident counts masked to zero: its workgroups
-// arrive together and never leave, so the tickets alone decide, and the split does not depend on
-// which of two simultaneous arrivals is seen first.
-POD_HD inline int role_for_arrival(uint32_t state, int p, int d, int unit = 0)
+// pattern; unit u therefore counts from kSlotsPerUnit * u, which spreads the pattern over the
+// chip (4:1 puts a decode workgroup on every fifth slot; 1:1 still gives every unit one of each).
+// The workgroups of the fused kernel arrive together and stay until the work is done, so the
+// ticket alone decides: the split does not depend on which of two simultaneous arrivals is seen
+// first, and there is no departure to account for.
+POD_HD inline int role_for_ticket(uint32_t ticket, int p, int d, int unit = 0)
 {
-    const int run_p = (int)(state & 1023u);
-    const int run_d = (int)((state >> 10) & 1023u);
-    const int ticket = (int)(state >> 20) + kSlotsPerUnit * unit;
-    const int lhs = run_p * d, rhs = run_d * p;
-    if (lhs < rhs) return kPrefill;
-    if (lhs > rhs) return kDecode;
-    return (ticket % (p + d)) < p ? kPrefill : kDecode;
+    const int t = (int)(ticket & 0xfffffu) + kSlotsPerUnit * unit;
+    return (t % (p + d)) < p ? kPrefill : kDecode;
 }
 
 // Optional execution trace: where each workgroup of an attention kernel ran, which operation it

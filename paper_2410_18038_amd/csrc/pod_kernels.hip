@@ -1199,10 +1199,8 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
     if (threadIdx.x == 0) {
         const unsigned cu = __smid() & (kCuSlots - 1);
-        const uint32_t state = atomicAdd(&hdr->cu_state[cu], kTicketOne);
-        const int role = role_for_arrival(state & ~(kTicketOne - 1u), a.p_ratio, a.d_ratio, (int)cu);
-        atomicAdd(&hdr->cu_state[cu], role == kPrefill ? kRunPrefillOne : kRunDecodeOne);
-        bind[0] = role;
+        const uint32_t ticket = atomicAdd(&hdr->cu_state[cu], 1u);
+        bind[0] = role_for_ticket(ticket, a.p_ratio, a.d_ratio, (int)cu);
         bind[2] = (int)cu;
     }
     __syncthreads();

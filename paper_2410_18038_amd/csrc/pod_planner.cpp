@@ -114,13 +114,21 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
             decode_row_used[(size_t)q_start] = 1;
         }
     }
+    // The prefill query ranges must tile [0, sum q_len): `out` holds exactly sum q_len prefill rows
+    // followed by the decode rows, so a gap would push the decode rows past the end of a buffer
+    // sized as documented, and an overlap would have two requests write one row.
     std::sort(spans.begin(), spans.end());
-    for (size_t i = 1; i < spans.size(); ++i)
-        if (spans[i - 1].first + spans[i - 1].second > spans[i].first) {
-            err = "prefill query ranges overlap";
+    int64_t next_row = 0;
+    for (size_t i = 0; i < spans.size(); ++i) {
+        if (spans[i].first != next_row) {
+            err = spans[i].first < next_row ? "prefill query ranges overlap"
+                                            : "prefill query ranges leave a gap (q_start must continue where the previous chunk ends)";
             return POD_ERR_INVALID_ARG;
         }
-    if (n_prefill_rows > (int64_t)1 << 30) { err = "too many prefill rows"; return POD_ERR_INVALID_ARG; }
+        next_row += spans[i].second;
+    }
+    // packed rows (token x head-in-group) are indexed with 32 bits
+    if (n_prefill_rows * group > (int64_t)1 << 30) { err = "too many prefill rows"; return POD_ERR_INVALID_ARG; }
 
     plan = Plan();
     plan.prm = prm;

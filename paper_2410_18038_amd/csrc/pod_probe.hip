@@ -1,6 +1,6 @@
 // Micro-kernels.  Two measure what this GPU can sustain: a coalesced HBM read stream and an MFMA
 // issue loop; the benchmark reports the attention kernels against these measured peaks next to
-// the datasheet ones.  A third group is the co-location experiment of the paper's Section 3.2
+// the datasheet ones.  A third group is the co-location experiment of the paper's Section 3.3
 // (a compute-bound and a memory-bound operation, run one after the other, fused by workgroup
 // index, and fused with roles bound per compute unit at run time).
 #include <hip/hip_runtime.h>
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kThreads) void mfma_loop_kernel(int iters, float *s
     if (s == 12345.678f) sink[0] = s;
 }
 
-// ---- co-location experiment (Section 3.2, Figure 7) -------------------------------------------
+// ---- co-location experiment (Section 3.3, Figure 7) -------------------------------------------
 // Compute item: every thread runs `iters` rounds of eight independent multiply-adds.  Memory
 // item: c = a + b over a chunk of n_vec 16-byte vectors, coalesced.  Both use 256 threads and
 // few registers, so eight workgroups of either kind fit on a compute unit.

@@ -27,7 +27,7 @@ KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
            "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_set_event_log",
            "pod_attn_plan_upload", "pod_attn_forward",
-           "pod_attn_simulate_binder", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
+           "pod_attn_role_for_ticket", "pod_attn_simulate_launch", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
            "pod_attn_plan_decode_queue",
            "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_colocation",
            "pod_attn_last_error", "pod_attn_version"]
@@ -97,9 +97,10 @@ def lib():
         L.pod_attn_forward.restype = ctypes.c_int
         L.pod_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        ctypes.c_int32, vp]
-        L.pod_attn_simulate_binder.restype = ctypes.c_int32
-        L.pod_attn_simulate_binder.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-                                               ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p]
+        L.pod_attn_role_for_ticket.restype = ctypes.c_int32
+        L.pod_attn_role_for_ticket.argtypes = [ctypes.c_int32] * 4
+        L.pod_attn_simulate_launch.restype = ctypes.c_int32
+        L.pod_attn_simulate_launch.argtypes = [vp, i32p, ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, i32p, i32p]
         L.pod_attn_plan_prefill_item.restype = ctypes.c_int
         L.pod_attn_plan_prefill_item.argtypes = [vp, ctypes.c_int32, i32p]
         L.pod_attn_plan_decode_unit.restype = ctypes.c_int
@@ -272,18 +273,24 @@ def pod_attn_probe_colocation(variant: int, a: int, b: int, c: int, bytes_per_it
                                            ctypes.c_void_p(counters), ctypes.c_void_p(sink), ctypes.c_void_p(stream)))
 
 
-def pod_attn_simulate_binder(n_prefill_items: int, n_decode_items: int, prefill_ratio: int,
-                             decode_ratio: int, events):
-    """Host model of the on-device binder; returns (served, roles, items) per arrival."""
-    ev, ev_p = _i32(np.asarray(events))
-    n_arr = int((ev >= 0).sum())
-    roles = np.full(max(n_arr, 1), -2, dtype=np.int32)
-    items = np.full(max(n_arr, 1), -2, dtype=np.int32)
-    served = lib().pod_attn_simulate_binder(
-        n_prefill_items, n_decode_items, prefill_ratio, decode_ratio, ev_p, int(ev.size),
-        roles.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
-        items.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
-    return int(served), roles[:n_arr], items[:n_arr]
+def pod_attn_role_for_ticket(ticket: int, prefill_ratio: int, decode_ratio: int, unit: int = 0) -> int:
+    return int(lib().pod_attn_role_for_ticket(ticket, prefill_ratio, decode_ratio, unit))
+
+
+def pod_attn_simulate_launch(plan: Plan, unit_of_wg, order):
+    """Host model of one fused launch; returns (steps, first_role, seat_of_wg, item_owner, unit_owner)."""
+    units, units_p = _i32(np.asarray(unit_of_wg))
+    order, order_p = _i32(np.asarray(order))
+    info = plan.info()
+    first = np.full(max(units.size, 1), -2, dtype=np.int32)
+    seat = np.full(max(units.size, 1), -1, dtype=np.int32)
+    items = np.full(max(info.n_prefill_items, 1), -2, dtype=np.int32)
+    dunits = np.full(max(info.n_decode_units, 1), -2, dtype=np.int32)
+    p = lambda a: a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    steps = lib().pod_attn_simulate_launch(plan.handle, units_p, int(units.size), order_p, int(order.size),
+                                           p(first), p(seat), p(items), p(dunits))
+    return (int(steps), first[:units.size], seat[:units.size], items[:info.n_prefill_items],
+            dunits[:info.n_decode_units])
 
 
 # ----------------------------------------------------------------------------------------------

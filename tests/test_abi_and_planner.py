@@ -1,4 +1,4 @@
-"""CPU tests of the C-ABI library: symbols, argument validation, the host planner, the binder model.
+"""CPU tests of the C-ABI library: symbols, argument validation, the host planner, the model of the device's claim protocol.
 
 No compute call is made here; the planner needs no GPU once n_compute_units is given.
 """
@@ -111,6 +111,9 @@ def test_invalid_arguments_are_rejected_with_a_message():
     expect(-1, meta=m)
     m = b.seq_meta.copy()
     m[0, 2] = 513                                                     # longer than the cache slot
+    expect(-1, meta=m)
+    m = b.seq_meta.copy()
+    m[0, 0] = 5                                                       # prefill rows must tile [0, sum q_len)
     expect(-1, meta=m)
 
 
@@ -338,16 +341,16 @@ def test_proportional_policy_reproduces_the_papers_example():
     plan = pod.pod_attn_plan_create(prm, meta)
     assert (plan.info().prefill_ratio, plan.info().decode_ratio) == (1, 1)
     plan.close()
-    # all arrivals on one compute unit, nobody leaves: roles must follow the printed pattern
-    served, roles, items = pod.pod_attn_simulate_binder(n_p, n_d, 1, 2, np.zeros(12, dtype=np.int32))
+    # all arrivals on one compute unit: their first operations follow the printed pattern
+    roles = [pod.pod_attn_role_for_ticket(t, 1, 2, 0) for t in range(12)]
     assert "".join("PD"[r] for r in roles) == pattern * 4
     # 50:50 alternates
     prm.policy = pod.POLICY_ALTERNATE
     plan = pod.pod_attn_plan_create(prm, meta)
     assert (plan.info().prefill_ratio, plan.info().decode_ratio) == (1, 1)
     plan.close()
-    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.zeros(6, dtype=np.int32))
-    assert "".join("PD"[r] for r in roles) == "PDPDPD"
+    assert "".join("PD"[pod.pod_attn_role_for_ticket(t, 1, 1, 0)] for t in range(6)) == "PDPDPD"
+    assert pod.pod_attn_role_for_ticket(-1, 1, 1, 0) == -1 and pod.pod_attn_role_for_ticket(0, 0, 0, 0) == -1
 
 
 def test_wave_quantization_example():
@@ -362,69 +365,91 @@ def test_wave_quantization_example():
         plan.close()
 
 
-@pytest.mark.parametrize("seed", range(6))
-def test_binder_hands_out_every_work_id_exactly_once(seed):
-    """Whatever unit each workgroup lands on and whenever others leave, prefill ids 0..P-1 and decode
-    ids 0..D-1 are each claimed once and nobody is left without work (Section 4.1: the scheme does
-    not depend on how the hardware places workgroups)."""
+def hardware_units(n_cus):
+    """Hardware unit ids as the device reports them: xcc << 6 | se << 4 | cu, 8 XCDs."""
+    per_xcd = max(1, -(-n_cus // 8))
+    return [((i // per_xcd) % 8) << 6 | ((i % per_xcd) // 8) << 4 | (i % per_xcd) % 8 for i in range(n_cus)]
+
+
+def launch_model_check(plan, placement, order):
+    info = plan.info()
+    steps, first, seat, items, units = pod.pod_attn_simulate_launch(plan, placement, order)
+    assert steps >= 0, "a work id was handed out twice" if steps == -2 else "bad arguments"
+    assert (items >= 0).all() and (items < len(placement)).all(), "a prefill item was never claimed"
+    assert (units >= 0).all() and (units < 4 * len(placement)).all(), "a decode unit was never claimed"
+    assert set(first.tolist()) <= {0, 1}
+    # seats are handed out once each, and the first seats (which carry the fixed units) are all taken
+    taken = sorted(x for x in seat.tolist() if x >= 0)
+    assert taken == list(range(len(taken)))
+    n_workers = min(info.n_compute_units, (info.n_decode_units + 3) // 4)
+    assert len(taken) >= min(n_workers, len(placement)) or info.n_decode_units == 0
+    # a fixed unit 4*s + v is run by wavefront v of the workgroup on seat s
+    n_fixed = plan.decode_queues()[0][0]
+    wg_of_seat = {int(x): w for w, x in enumerate(seat.tolist()) if x >= 0}
+    for u in range(n_fixed):
+        assert units[u] == 4 * wg_of_seat[u // 4] + u % 4
+    return first, seat, items, units
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_device_claim_protocol_hands_out_every_work_id_exactly_once(seed):
+    """The protocol the fused kernel runs (ticket, decode seats with fixed first units, per-XCD queues
+    with a walk over the other queues, one switch of operation), under random placements of the
+    workgroups on hardware units and random interleavings of their steps: every prefill item and
+    every decode unit is run exactly once and the launch drains (Section 4.1: the scheme does not
+    depend on how the hardware places workgroups)."""
     rng = np.random.Generator(np.random.PCG64(seed))
-    n_p, n_d = int(rng.integers(0, 300)), int(rng.integers(0, 900))
+    n_cus = int(rng.choice([1, 3, 64, 256]))
+    n_p, n_d = int(rng.integers(0, 4)), int(rng.integers(0, 50))
     if n_p + n_d == 0:
-        n_d = 5
-    p_ratio, d_ratio = int(rng.integers(1, 5)), int(rng.integers(1, 9))
-    if n_p == 0:
-        p_ratio = 0
-    if n_d == 0:
-        d_ratio = 0
-    n_units = int(rng.choice([1, 7, 256]))
-    events, alive, arrivals = [], [], 0
-    while arrivals < n_p + n_d:
-        if alive and rng.random() < 0.45:
-            who = alive.pop(int(rng.integers(len(alive))))
-            events.append(-who - 1)
+        n_d = 3
+    prefill = [(int(q), int(q + pre)) for q, pre in zip(rng.integers(1, 1500, n_p), rng.integers(0, 6000, n_p))]
+    decodes = rng.integers(1, 9000, n_d).tolist()
+    hkv = int(rng.choice([1, 2, 8]))
+    prm, meta = meta_only(f"model{seed}", prefill, decodes, hq=hkv * int(rng.choice([1, 4])), hkv=hkv)
+    prm.n_compute_units = n_cus
+    prm.decode_chunk = int(rng.choice([0, 64, 512]))
+    prm.policy = int(rng.integers(0, 3))
+    plan = pod.pod_attn_plan_create(prm, meta)
+    grid = plan.info().fused_grid
+    hw = hardware_units(n_cus)
+    for trial in range(4):
+        # placements: two per unit in order; random units (some crowded, some empty); all on one unit
+        if trial == 0:
+            placement = [hw[(w // 2) % n_cus] for w in range(grid)]
+        elif trial == 3:
+            placement = [hw[0]] * grid
         else:
-            events.append(int(rng.integers(n_units)) * 3 % 1024)
-            alive.append(arrivals)
-            arrivals += 1
-    served, roles, items = pod.pod_attn_simulate_binder(n_p, n_d, p_ratio, d_ratio, np.array(events, dtype=np.int32))
-    assert served == n_p + n_d and (roles >= 0).all()
-    assert sorted(items[roles == 0].tolist()) == list(range(n_p))
-    assert sorted(items[roles == 1].tolist()) == list(range(n_d))
-    # one arrival too many gets nothing
-    served2, roles2, items2 = pod.pod_attn_simulate_binder(n_p, n_d, p_ratio, d_ratio,
-                                                           np.array(events + [0], dtype=np.int32))
-    assert served2 == served and roles2[-1] == -1 and items2[-1] == -1
+            placement = [hw[int(rng.integers(n_cus))] for _ in range(grid)]
+        # interleavings: none (pure round-robin drain), or a long random sequence of actors, or
+        # one straggler workgroup that only moves when everybody else is done
+        if trial == 0:
+            order = []
+        elif trial == 1:
+            order = rng.integers(0, 4 * max(grid, 1), size=20000).tolist()
+        else:
+            order = [a for a in rng.integers(0, 4 * max(grid, 1), size=20000).tolist() if a // 4 != 0]
+        launch_model_check(plan, placement, order)
+    plan.close()
 
 
-def test_binder_keeps_both_operations_resident_on_each_unit():
-    """Two slots per unit, long prefill items, short decode workgroups: every unit keeps one of each
-    while both kinds of work remain, which the plain ticket rule alone would not do."""
-    n_units, n_p, n_d = 4, 8, 200
-    events, resident = [], {u: [] for u in range(n_units)}    # unit -> list of (arrival, role unknown yet)
-    roles_so_far = []
-    arrivals = 0
-    # fill both slots of every unit
-    for u in range(n_units):
-        for _ in range(2):
-            events.append(u)
-            resident[u].append(arrivals)
-            arrivals += 1
-    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
-    for u in range(n_units):
-        assert sorted(roles[resident[u]].tolist()) == [0, 1]
-    # decode workgroups finish and are replaced 20 times per unit; prefill ones stay
-    for _ in range(20):
-        for u in range(n_units):
-            _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
-            leaving = [a for a in resident[u] if roles[a] == 1][0]
-            events.append(-leaving - 1)
-            resident[u].remove(leaving)
-            events.append(u)
-            resident[u].append(arrivals)
-            arrivals += 1
-    _, roles, _ = pod.pod_attn_simulate_binder(n_p, n_d, 1, 1, np.array(events, dtype=np.int32))
-    for u in range(n_units):
-        assert sorted(roles[resident[u]].tolist()) == [0, 1]
+def test_every_unit_gets_one_workgroup_of_each_operation():
+    """With two workgroups per unit and a 1:1 ratio (what the automatic policy plans for every
+    benchmark batch) each unit's two tickets give it one prefill-first and one decode-first
+    workgroup, whichever arrives first; the decode-first ones take the seats."""
+    prm, meta = meta_only("c2", [(1024, 4096)], [4096] * 64, hq=32, hkv=32, block_size=0)
+    plan = pod.pod_attn_plan_create(prm, meta)
+    info = plan.info()
+    assert (info.prefill_ratio, info.decode_ratio, info.fused_grid) == (1, 1, 512)
+    hw = hardware_units(256)
+    rng = np.random.Generator(np.random.PCG64(5))
+    placement = [hw[w % 256] for w in range(512)]          # the hardware deals round-robin
+    first, seat, items, units = launch_model_check(plan, placement, rng.integers(0, 2048, size=50000).tolist())
+    for u in range(256):
+        assert sorted([int(first[u]), int(first[u + 256])]) == [0, 1]
+    # decode-first workgroups hold all 256 seats unless a prefill-first one ran out of items earlier
+    assert (seat >= 0).all()
+    plan.close()
 
 
 def test_decode_last_piece_is_cut_into_half_and_quarters():
@@ -453,14 +478,10 @@ def test_binder_spreads_a_long_pattern_over_the_units():
     every fifth slot of the chip starts in the decode operation, and with 1 : 1 every unit still
     gets one of each (Section 4.1's ticket rule, applied chip-wide)."""
     n_units = 40
-    events = np.array([u for u in range(n_units) for _ in range(2)], dtype=np.int32)
-    _, roles, _ = pod.pod_attn_simulate_binder(10 ** 6, 10 ** 6, 4, 1, events)
-    # resident counts steer the second arrival of a unit towards the missing operation; the
-    # device masks them, so model that by looking at first arrivals only, then at the ticket rule
-    first = roles[0::2]
-    assert first.tolist() == [0 if (2 * u) % 5 < 4 else 1 for u in range(n_units)]
-    _, roles11, _ = pod.pod_attn_simulate_binder(10 ** 6, 10 ** 6, 1, 1, events)
-    assert all(sorted(roles11[2 * u:2 * u + 2].tolist()) == [0, 1] for u in range(n_units))
+    slots = [pod.pod_attn_role_for_ticket(t, 4, 1, u) for u in range(n_units) for t in range(2)]
+    assert slots == [0 if s % 5 < 4 else 1 for s in range(2 * n_units)]
+    for u in range(n_units):
+        assert sorted(pod.pod_attn_role_for_ticket(t, 1, 1, u) for t in range(2)) == [0, 1]
 
 
 def test_event_log_and_queue_arguments_are_checked():

@@ -331,7 +331,7 @@ def test_chunk_series_batches_on_sampled_rows(model, n_decode, chunk):
 
 
 def test_colocation_probe_moves_every_chunk_once():
-    """The co-location experiment (Section 3.2): every variant of the fused launch computes c = a + b
+    """The co-location experiment (Section 3.3): every variant of the fused launch computes c = a + b
     over every chunk exactly once, whatever the binding, and the per-unit binder claims every item."""
     n_items, item_bytes = 700, 16 * 1000
     a = torch.arange(n_items * item_bytes // 4, dtype=torch.float32, device="cuda:0")
@@ -382,4 +382,37 @@ def test_forward_can_be_captured_in_a_graph_and_replayed(mode):
         again = attn.forward(dev_batch, mode=pod.MODES[mode])              # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(again.view(torch.int16), eager.view(torch.int16))
+    attn.close()
+
+
+@pytest.mark.parametrize("config", [2, 4])
+def test_both_operations_are_resident_on_every_compute_unit(config):
+    """Section 4.1's guarantee, read off the library's own records of one fused launch of a
+    benchmark batch (parity cannot see placement): at least 95 % of the hardware units that took
+    part hold one workgroup that started with prefill and one that started with decode; every
+    prefill item and decode unit ran exactly once; and on at least 95 % of the units a decode unit
+    was streaming while a prefill item was running on the same unit."""
+    from paper_2410_18038_amd import trace_report
+    batch = wl.config_batch(config, device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    plain = attn.forward(batch).clone()
+    attn.enable_trace()
+    attn.enable_event_log()
+    traced = attn.forward(batch)
+    trace, events = attn.read_trace(), attn.read_event_log()
+    assert torch.equal(plain.view(torch.int16), traced.view(torch.int16))
+    info = attn.info
+    rep = trace_report.colocation(trace, events, info.n_prefill_items, info.n_decode_units)
+    print(trace_report.as_text(batch.name, rep), flush=True)
+    assert rep["workgroups"] == info.fused_grid == 2 * info.n_compute_units
+    assert rep["hardware_units"] >= 0.95 * info.n_compute_units
+    assert rep["units_with_both_first_roles"] >= 0.95 * rep["hardware_units"]
+    assert rep["prefill_items_logged_once"] and rep["decode_units_logged_once"]
+    assert rep["units_where_roles_overlap_in_time"] >= 0.95 * rep["hardware_units"]
+    # configuration 2's items all run beside the decode stream; configuration 4's prefill outlasts it
+    assert rep["share_of_prefill_time_with_decode_on_same_unit"] > (0.8 if config == 2 else 0.2)
+    # the records of the workgroups agree with the plan: prefill items are counted per workgroup
+    n_items = int(trace["n_first"][trace["first_role"] == 0].sum() + trace["n_second"][trace["first_role"] == 1].sum())
+    assert n_items == info.n_prefill_items
+    assert (trace["t_switch"] >= trace["t_begin"]).all() and (trace["t_end"] >= trace["t_switch"]).all()
     attn.close()
