@@ -223,6 +223,32 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
                             int32_t mode, void *stream);
 
 /*
+ * The same call for callers that cannot allocate device memory or be handed a workspace: code
+ * under HIP graph capture set-ups that forbid allocation, tight serving loops, harnesses that
+ * forbid hipMalloc.  Everything pod_attn_forward keeps in the caller's workspace (counters, work
+ * tables, split-KV partials) lives in a fixed array inside the library instead: device memory of
+ * POD_ATTN_STATIC_SCRATCH_BYTES bytes that every GPU the library runs on holds from the moment the
+ * library's code is loaded there until the process ends.  The call allocates nothing and frees
+ * nothing (no hipMalloc, hipFree, stream or event creation): it launches kernels on `stream`, and,
+ * whenever the array does not already hold this plan's work tables (the first call with a plan
+ * on a GPU, or after a call with another plan there), it first clears the array's counters with a
+ * kernel and copies the tables in with hipMemcpyAsync, waiting for those copies.  No
+ * pod_attn_plan_upload is needed.  Arguments, results and modes are those of pod_attn_forward,
+ * except:
+ *   - a plan whose pod_attn_workspace_size exceeds POD_ATTN_STATIC_SCRATCH_BYTES is rejected with
+ *     POD_ERR_WORKSPACE (the message gives both numbers) and nothing is launched;
+ *   - POD_MODE_STREAMS is rejected with POD_ERR_UNSUPPORTED (it creates streams and events).
+ * All calls on one GPU share that GPU's array: two calls of this entry point on the same GPU must
+ * not overlap in time (not from two streams, not from two host threads); calls on different
+ * GPUs are independent.  pod_attn_forward and its workspaces are not affected in any way.
+ */
+#define POD_ATTN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+pod_status pod_attn_forward_static(const void *prefill_q, const void *decode_q,
+                                   const void *k_cache, const void *v_cache,
+                                   const int32_t *seq_meta, const int32_t *block_table,
+                                   void *out, const pod_attn_plan *plan, int32_t mode, void *stream);
+
+/*
  * The role rule of the on-device binder (Section 4.1, the scheduling listing), host-callable for
  * tests: the first operation of the workgroup that holds `ticket` (arrivals on its hardware unit
  * before it, counted from 0) on unit `unit`: 0 prefill when (ticket + 2 * unit) mod (p + d) < p,

@@ -2,8 +2,10 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -15,11 +17,18 @@
 
 struct pod_attn_plan {
     pod::Plan p;
+    uint64_t serial = 0;                    // unique per plan object of this process, never reused
 };
 
 namespace {
 
 thread_local std::string g_last_error;
+std::atomic<uint64_t> g_next_plan_serial{1};
+
+// Which plan's work tables each GPU's static scratch holds (0 = none), for pod_attn_forward_static.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+uint64_t g_static_owner[kMaxDevices] = {0};
 
 pod_status fail(pod_status code, const std::string &msg)
 {
@@ -106,6 +115,30 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     return a;
 }
 
+// Clear the counters at the head of `workspace` (with a kernel, not a memset) and copy the plan's
+// work tables behind them; returns when the copies have completed.
+pod_status upload_tables(const pod::Plan &p, void *workspace, hipStream_t s)
+{
+    unsigned char *ws = (unsigned char *)workspace;
+    hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
+    if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
+    struct Part { size_t off; const void *src; size_t bytes; };
+    const Part parts[5] = {
+        {p.off_dq, p.dq_begin, sizeof p.dq_begin},
+        {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
+        {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
+        {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)},
+        {p.off_crows, p.crows.data(), p.crows.size() * sizeof(int32_t)}};
+    for (const Part &part : parts) {
+        if (part.bytes == 0) continue;
+        e = hipMemcpyAsync(ws + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s);
+        if (e != hipSuccess) return fail_hip(e, "copying plan tables");
+    }
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "waiting for plan upload");
+    return POD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -133,6 +166,7 @@ pod_status pod_attn_plan_create(const pod_attn_params *params, const int32_t *se
         delete obj;
         return fail(st, err);
     }
+    obj->serial = g_next_plan_serial.fetch_add(1);
     *plan = obj;
     return POD_OK;
 }
@@ -227,31 +261,13 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
     const pod::Plan &p = plan->p;
     if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
     if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
-    hipStream_t s = (hipStream_t)stream;
-    unsigned char *ws = (unsigned char *)workspace;
-    hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
-    if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
-    struct Part { size_t off; const void *src; size_t bytes; };
-    const Part parts[5] = {
-        {p.off_dq, p.dq_begin, sizeof p.dq_begin},
-        {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
-        {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
-        {p.off_centries, p.centries.data(), p.centries.size() * sizeof(pod::CombineEntry)},
-        {p.off_crows, p.crows.data(), p.crows.size() * sizeof(int32_t)}};
-    for (const Part &part : parts) {
-        if (part.bytes == 0) continue;
-        e = hipMemcpyAsync(ws + part.off, part.src, part.bytes, hipMemcpyHostToDevice, s);
-        if (e != hipSuccess) return fail_hip(e, "copying plan tables");
-    }
-    e = hipStreamSynchronize(s);
-    if (e != hipSuccess) return fail_hip(e, "waiting for plan upload");
-    return POD_OK;
+    return upload_tables(p, workspace, (hipStream_t)stream);
 }
 
-pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const void *k_cache,
-                            const void *v_cache, const int32_t *seq_meta, const int32_t *block_table,
-                            void *out, const pod_attn_plan *plan, void *workspace,
-                            size_t workspace_bytes, int32_t mode, void *stream)
+static pod_status forward_impl(const void *prefill_q, const void *decode_q, const void *k_cache,
+                               const void *v_cache, const int32_t *seq_meta, const int32_t *block_table,
+                               void *out, const pod_attn_plan *plan, void *workspace,
+                               size_t workspace_bytes, int32_t mode, void *stream, bool use_static)
 {
     if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
     pod::Plan &p = const_cast<pod_attn_plan *>(plan)->p;
@@ -265,13 +281,41 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     if (p.prm.n_prefill > 0 && !prefill_q) return fail(POD_ERR_INVALID_ARG, "prefill_q is null");
     if (p.prm.n_decode > 0 && !decode_q) return fail(POD_ERR_INVALID_ARG, "decode_q is null");
     if (paged && !block_table) return fail(POD_ERR_INVALID_ARG, "block_table is null for a paged cache");
-    if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
-    if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    if (use_static) {
+        if (mode == POD_MODE_STREAMS)
+            return fail(POD_ERR_UNSUPPORTED, "the two-stream mode creates streams and events; it is not available "
+                                             "from the entry point that allocates nothing");
+        if (p.ws_bytes > pod::kStaticScratchBytes)
+            return fail(POD_ERR_WORKSPACE, "this batch needs " + std::to_string(p.ws_bytes) + " bytes of workspace, the "
+                        "library's static scratch holds " + std::to_string(pod::kStaticScratchBytes) +
+                        ": use pod_attn_forward with a workspace of the caller's");
+    } else {
+        if (!workspace || workspace_bytes < p.ws_bytes) return fail(POD_ERR_WORKSPACE, "workspace missing or too small");
+        if (((uintptr_t)workspace & 255u) != 0) return fail(POD_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    }
     // every row is read and written in 16-byte pieces
     if ((((uintptr_t)prefill_q | (uintptr_t)decode_q | (uintptr_t)k_cache | (uintptr_t)v_cache | (uintptr_t)out) & 15u) != 0)
         return fail(POD_ERR_INVALID_ARG, "prefill_q, decode_q, k_cache, v_cache and out must be 16-byte aligned");
     if ((((uintptr_t)seq_meta | (uintptr_t)block_table) & 3u) != 0)
         return fail(POD_ERR_INVALID_ARG, "seq_meta and block_table must be 4-byte aligned");
+    if (use_static) {
+        // This GPU's copy of the static array.  It is shared by every call on the GPU and keeps the
+        // last call's contents: when it holds another plan's tables (or none), the counters are
+        // cleared and this plan's tables copied in before the launch.
+        int dev = 0;
+        hipError_t de = hipGetDevice(&dev);
+        if (de != hipSuccess) return fail_hip(de, "asking for the current device");
+        if (dev < 0 || dev >= kMaxDevices) return fail(POD_ERR_UNSUPPORTED, "device index beyond what the static scratch tracks");
+        de = pod::static_scratch(&workspace);
+        if (de != hipSuccess) return fail_hip(de, "looking up the static scratch of this device");
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        if (g_static_owner[dev] != plan->serial) {
+            g_static_owner[dev] = 0;
+            const pod_status up = upload_tables(p, workspace, (hipStream_t)stream);
+            if (up != POD_OK) return up;
+            g_static_owner[dev] = plan->serial;
+        }
+    }
 
     pod::KernelArgs a = make_args(p, prefill_q, decode_q, k_cache, v_cache, seq_meta, block_table, out, workspace);
     hipStream_t s = (hipStream_t)stream;
@@ -343,6 +387,25 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const v
     if (e != hipSuccess) return fail_hip(e, "launching attention kernels");
     return POD_OK;
 }
+
+pod_status pod_attn_forward(const void *prefill_q, const void *decode_q, const void *k_cache,
+                            const void *v_cache, const int32_t *seq_meta, const int32_t *block_table,
+                            void *out, const pod_attn_plan *plan, void *workspace,
+                            size_t workspace_bytes, int32_t mode, void *stream)
+{
+    return forward_impl(prefill_q, decode_q, k_cache, v_cache, seq_meta, block_table, out, plan, workspace,
+                        workspace_bytes, mode, stream, false);
+}
+
+pod_status pod_attn_forward_static(const void *prefill_q, const void *decode_q, const void *k_cache,
+                                   const void *v_cache, const int32_t *seq_meta, const int32_t *block_table,
+                                   void *out, const pod_attn_plan *plan, int32_t mode, void *stream)
+{
+    return forward_impl(prefill_q, decode_q, k_cache, v_cache, seq_meta, block_table, out, plan, nullptr, 0,
+                        mode, stream, true);
+}
+
+static_assert(pod::kStaticScratchBytes == POD_ATTN_STATIC_SCRATCH_BYTES, "the header states the size of the static scratch");
 
 int32_t pod_attn_role_for_ticket(int32_t ticket, int32_t prefill_ratio, int32_t decode_ratio, int32_t unit)
 {

@@ -8,6 +8,7 @@
 // wants for its P operand, and the running max and sum of a row are per-lane scalars.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "pod_common.h"
@@ -1370,6 +1371,33 @@ hipError_t clear_header(WsHeader *hdr, hipStream_t stream)
 {
     clear_header_kernel<<<dim3(1), dim3(256), 0, stream>>>(hdr);
     return hipGetLastError();
+}
+
+// Workspace of the entry point that allocates nothing.  In host code the name below is only a
+// handle for the symbol, not a device address: the address of each GPU's copy comes from
+// hipGetSymbolAddress, once per device with that device current, and only that address is ever
+// handed to kernels and copies.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+hipError_t static_scratch(void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *per_device[kMaxDevices] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
 }
 
 }  // namespace pod

@@ -13,4 +13,10 @@ hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool 
 // Zero the counters at the head of a workspace.
 hipError_t clear_header(WsHeader *hdr, hipStream_t stream);
 
+// The library's own workspace for callers that may not allocate: a fixed array in device memory,
+// one copy per GPU, held from the moment the library is loaded on that GPU until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+// Address of the current device's copy (looked up once per device, then remembered).
+hipError_t static_scratch(void **ptr);
+
 }  // namespace pod

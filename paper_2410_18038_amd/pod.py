@@ -26,7 +26,7 @@ KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
            "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_set_event_log",
-           "pod_attn_plan_upload", "pod_attn_forward",
+           "pod_attn_plan_upload", "pod_attn_forward", "pod_attn_forward_static",
            "pod_attn_role_for_ticket", "pod_attn_simulate_launch", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
            "pod_attn_plan_decode_queue",
            "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_colocation",
@@ -97,6 +97,8 @@ def lib():
         L.pod_attn_forward.restype = ctypes.c_int
         L.pod_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t,
                                        ctypes.c_int32, vp]
+        L.pod_attn_forward_static.restype = ctypes.c_int
+        L.pod_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp]
         L.pod_attn_role_for_ticket.restype = ctypes.c_int32
         L.pod_attn_role_for_ticket.argtypes = [ctypes.c_int32] * 4
         L.pod_attn_simulate_launch.restype = ctypes.c_int32
@@ -248,6 +250,17 @@ def pod_attn_forward(prefill_q: int, decode_q: int, k_cache: int, v_cache: int, 
     _check(lib().pod_attn_forward(vp(prefill_q), vp(decode_q), vp(k_cache), vp(v_cache), vp(seq_meta),
                                   vp(block_table), vp(out), plan.handle, vp(workspace), workspace_bytes,
                                   mode, vp(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def pod_attn_forward_static(prefill_q: int, decode_q: int, k_cache: int, v_cache: int, seq_meta: int,
+                            block_table: int, out: int, plan: Plan, mode: int = MODE_FUSED, stream: int = 0):
+    """pod_attn_forward on the library's own static scratch: no workspace argument, no allocation."""
+    vp = ctypes.c_void_p
+    _check(lib().pod_attn_forward_static(vp(prefill_q), vp(decode_q), vp(k_cache), vp(v_cache), vp(seq_meta),
+                                         vp(block_table), vp(out), plan.handle, mode, vp(stream)))
 
 
 def pod_attn_probe_hbm_read(buf: int, nbytes: int, sink: int, stream: int = 0):
