@@ -430,6 +430,9 @@ def main():
                     help="instead of a configuration, run the co-location experiment of the paper's Section 3.3: "
                          "a compute-bound and a memory-bound operation serially, on two streams, fused by "
                          "workgroup index and fused with per-compute-unit binding")
+    ap.add_argument("--issue-probe", action="store_true",
+                    help="instead of a configuration, time the instruction-mix probes (matrix instructions alone "
+                         "and beside softmax-like vector work, one and two wavefronts per SIMD) and print a table")
     ap.add_argument("--trace-summary", action="store_true",
                     help="instead of timing, run one fused launch of --config with the library's workgroup trace "
                          "and event log switched on and print where and when the two operations ran (text)")
@@ -460,6 +463,22 @@ def main():
 
     if args.colocation:
         print(json.dumps(run_colocation(args.steps, args.warmup, torch, pod)), flush=True)
+        return
+    if args.issue_probe:
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+        print("instruction-mix probe: ns per matrix instruction, per wavefront and per SIMD (32x32x16 bf16; 32 cycles "
+              "at full rate)")
+        for variant, name in enumerate(pod.ISSUE_PROBE_VARIANTS):
+            for w in (1, 2):
+                n = [0.0]
+
+                def go():
+                    n[0] = pod.pod_attn_probe_issue(variant, 20000, w, sink.data_ptr(),
+                                                    torch.cuda.current_stream().cuda_stream)
+                go()
+                t = float(np.min(event_times_us(go, 5, torch)))
+                print(f"  {variant} {name:82s} {w} wavefront(s)/SIMD: {t * 1e3 / n[0]:6.2f} per wavefront, "
+                      f"{t * 1e3 / n[0] / w:6.2f} per SIMD")
         return
     if args.trace_summary:
         from paper_2410_18038_amd import trace_report

@@ -319,6 +319,28 @@ pod_status pod_attn_probe_hbm_read(const void *buf, size_t bytes, void *sink, vo
 pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, void *stream);
 
 /*
+ * What one SIMD overlaps (Section 4.2.1 sizes the tiles by how much vector work runs beside the
+ * tensor-core work; this measures the same trade on this chip).  Enqueues one kernel in which
+ * every wavefront of `wgs_per_unit` (1 or 2) workgroups of 256 threads per compute unit, i.e. one
+ * or two wavefronts per SIMD, runs `iters` rounds of a fixed instruction mix:
+ *   0  four dense bf16 32x32x16 matrix instructions
+ *   1  the same, each followed by one 2^x
+ *   2  each followed by the vector work of one softmax score: 2^x, two multiply-adds, one
+ *      two-to-one rounding to bf16, one three-way maximum
+ *   3  mix 2 plus one two-element dot product (the weight sum taken over the rounded pairs)
+ *   4  each followed by one two-element dot product only
+ *   5  a software-pipelined turn, three per round: one 16-byte LDS read, one matrix instruction,
+ *      and the softmax work of one score in three stages one turn apart
+ *   6  the same turn with two matrix instructions per LDS read and the work of two scores (a
+ *      wavefront that holds two row blocks)
+ * *matrix_ops_per_wave (host, may be NULL) receives the matrix instructions one wavefront issued;
+ * the caller times the kernel.  `sink`: 4 writable bytes of device memory, never written in
+ * practice.  Returns POD_ERR_INVALID_ARG for an unknown variant or bad arguments.
+ */
+pod_status pod_attn_probe_issue(int32_t variant, int32_t iters, int32_t wgs_per_unit, void *sink,
+                                double *matrix_ops_per_wave, void *stream);
+
+/*
  * The co-location experiment of Section 3.3 (Figure 7), independent of attention: a compute-bound
  * operation (n_compute_items workgroups' worth of multiply-add loops, compute_iters rounds each)
  * and a memory-bound one (c = a + b over n_memory_items chunks of bytes_per_item bytes per array),

@@ -147,6 +147,105 @@ __global__ __launch_bounds__(kThreads) void colo_fused_bound_kernel(ColoArgs g)
     else if (pick[0] == 1) colo_memory(g, pick[1]);
 }
 
+
+// ---- instruction-mix probe ------------------------------------------------------------------
+// What a SIMD of this chip can overlap: dense matrix instructions alone, and beside the vector
+// work a softmax does per score (scale-and-shift, 2^x, a maximum, rounding to 16 bit, the weight
+// sum), with the sum taken either by plain additions or by two-element dot products.  The
+// prefill loop's choices (where its time goes, why the weight sum matters, why one wavefront per
+// SIMD with a wider tile does not pay) rest on these figures.  Every variant is a loop over
+// "turns"; the mix of a turn is fixed at compile time and held in place by scheduling barriers.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int NM, int NE, int NF, int NC, int NX, int ND>
+__global__ __launch_bounds__(kThreads) void issue_mix_kernel(int iters, float seed, float *sink)
+{
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = seed * (float)(i + r);
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(seed + (float)i); b[i] = (__bf16)(seed * (float)i); }
+    float e[8], f[8], m[4], d[2];
+    uint32_t c[4];
+    for (int i = 0; i < 8; ++i) { e[i] = seed * (float)(threadIdx.x + i) * 1e-3f; f[i] = seed + (float)i; }
+    for (int i = 0; i < 4; ++i) { m[i] = seed - (float)i; c[i] = (uint32_t)i; }
+    d[0] = d[1] = seed;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < NM; ++t) {
+            acc[t & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t & 3], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NE; ++i) asm volatile("v_exp_f32 %0, %0" : "+v"(e[(t * NE + i) & 7]));
+#pragma unroll
+            for (int i = 0; i < NF; ++i) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(f[(t * NF + i) & 7]) : "v"(seed));
+#pragma unroll
+            for (int i = 0; i < NC; ++i)
+                asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(c[(t * NC + i) & 3]) : "v"(f[(i + 4) & 7]), "v"(e[(i + 4) & 7]));
+#pragma unroll
+            for (int i = 0; i < NX; ++i)
+                asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(m[(t * NX + i) & 3]) : "v"(f[(i + 5) & 7]), "v"(e[(i + 5) & 7]));
+#pragma unroll
+            for (int i = 0; i < ND; ++i)
+                asm volatile("v_dot2_f32_bf16 %0, %1, %2, %0" : "+v"(d[i & 1]) : "v"(c[(i + 2) & 3]), "v"(c[(i + 3) & 3]));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = d[0] + d[1];
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    for (int i = 0; i < 8; ++i) s += e[i] + f[i];
+    for (int i = 0; i < 4; ++i) s += m[i] + (float)c[i];
+    if (s == 12345.678f) sink[0] = s;
+}
+
+// A turn of a software-pipelined tile loop: one 16-byte LDS fragment read (three turns ahead), NMF
+// matrix instructions that share the fragment, and the softmax work of NMF scores per lane in
+// three stages that are one turn apart, so that no instruction depends on a result of its own turn.
+template <int NMF>
+__global__ __launch_bounds__(kThreads) void issue_turn_kernel(int iters, float seed, float *sink)
+{
+    __shared__ u32x4 lds[1024];
+    for (int i = threadIdx.x; i < 1024; i += kThreads) lds[i] = u32x4{1u, 2u, 3u, (uint32_t)i};
+    __syncthreads();
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) acc[i][r] = seed * (float)(i + r);
+    bf16x8 b;
+    for (int i = 0; i < 8; ++i) b[i] = (__bf16)(seed * (float)i);
+    float s1[NMF], s2[NMF], s3[NMF], lsum = 0.f, mx = seed;
+    uint32_t pw = 0;
+    for (int i = 0; i < NMF; ++i) { s1[i] = seed * (float)i; s2[i] = seed + (float)i; s3[i] = seed - (float)i; }
+    u32x4 frag[3];
+    const __attribute__((address_space(3))) u32x4 *lp = (const __attribute__((address_space(3))) u32x4 *)lds + (threadIdx.x & 63);
+    frag[0] = lp[0]; frag[1] = lp[64]; frag[2] = lp[128];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const bf16x8 a = __builtin_bit_cast(bf16x8, frag[t]);
+#pragma unroll
+            for (int mm = 0; mm < NMF; ++mm)
+                acc[(t * NMF + mm) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[(t * NMF + mm) & 3], 0, 0, 0);
+            frag[t] = lp[((it * 3 + t) & 15) * 64];            // lands in the register it is used from, three turns on
+#pragma unroll
+            for (int mm = 0; mm < NMF; mm += 2)
+                asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(pw) : "v"(s3[mm]), "v"(s3[(mm + 1) % NMF]));
+#pragma unroll
+            for (int mm = 0; mm < NMF; ++mm) asm volatile("v_add_f32 %0, %0, %1" : "+v"(lsum) : "v"(s3[mm]));
+#pragma unroll
+            for (int mm = 0; mm < NMF; ++mm) asm volatile("v_exp_f32 %0, %1" : "=v"(s3[mm]) : "v"(s2[mm]));
+#pragma unroll
+            for (int mm = 0; mm < NMF; ++mm) asm volatile("v_fma_f32 %0, %1, %2, %2" : "=v"(s2[mm]) : "v"(s1[mm]), "v"(seed));
+#pragma unroll
+            for (int mm = 0; mm < NMF; ++mm) asm volatile("v_max_f32 %0, %0, %1" : "+v"(mx) : "v"(s1[mm]));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = lsum + mx + (float)pw;
+    for (int i = 0; i < 4; ++i)
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -171,6 +270,31 @@ pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, voi
     const int grid = cus * 2;                       // 8 wavefronts per compute unit, 2 per SIMD
     mfma_loop_kernel<<<dim3(grid), dim3(kThreads), 0, (hipStream_t)stream>>>(iters, (float *)sink);
     if (flops_out) *flops_out = (double)grid * (kThreads / 64) * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+    return hipGetLastError() == hipSuccess ? POD_OK : POD_ERR_HIP;
+}
+
+pod_status pod_attn_probe_issue(int32_t variant, int32_t iters, int32_t wgs_per_unit, void *sink,
+                                double *matrix_ops_per_wave, void *stream)
+{
+    if (!sink || iters <= 0 || wgs_per_unit < 1 || wgs_per_unit > 2) return POD_ERR_INVALID_ARG;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) != hipSuccess) return POD_ERR_HIP;
+    (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const dim3 grid(cus * wgs_per_unit), block(kThreads);
+    hipStream_t s = (hipStream_t)stream;
+    float *out = (float *)sink;
+    double per_iter = 4.0;
+    switch (variant) {
+    case 0: issue_mix_kernel<4, 0, 0, 0, 0, 0><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
+    case 1: issue_mix_kernel<4, 1, 0, 0, 0, 0><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
+    case 2: issue_mix_kernel<4, 1, 2, 1, 1, 0><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
+    case 3: issue_mix_kernel<4, 1, 2, 1, 1, 1><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
+    case 4: issue_mix_kernel<4, 0, 0, 0, 0, 1><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
+    case 5: issue_turn_kernel<1><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 3.0; break;
+    case 6: issue_turn_kernel<2><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 6.0; break;
+    default: return POD_ERR_INVALID_ARG;
+    }
+    if (matrix_ops_per_wave) *matrix_ops_per_wave = per_iter * (double)iters;
     return hipGetLastError() == hipSuccess ? POD_OK : POD_ERR_HIP;
 }
 

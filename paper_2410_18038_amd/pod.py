@@ -29,7 +29,7 @@ EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_
            "pod_attn_plan_upload", "pod_attn_forward", "pod_attn_forward_static",
            "pod_attn_role_for_ticket", "pod_attn_simulate_launch", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
            "pod_attn_plan_decode_queue",
-           "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_colocation",
+           "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_issue", "pod_attn_probe_colocation",
            "pod_attn_last_error", "pod_attn_version"]
 
 
@@ -114,6 +114,9 @@ def lib():
         L.pod_attn_probe_hbm_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         L.pod_attn_probe_mfma.restype = ctypes.c_int
         L.pod_attn_probe_mfma.argtypes = [ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pod_attn_probe_issue.restype = ctypes.c_int
+        L.pod_attn_probe_issue.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp,
+                                           ctypes.POINTER(ctypes.c_double), vp]
         L.pod_attn_probe_colocation.restype = ctypes.c_int
         L.pod_attn_probe_colocation.argtypes = [ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, ctypes.c_int32,
                                                 ctypes.c_int32, ctypes.c_int32, vp, vp, vp]
@@ -277,6 +280,22 @@ def pod_attn_probe_mfma(iters: int, sink: int, stream: int = 0) -> float:
     if status != POD_OK:
         raise PodError(status, "pod_attn_probe_mfma failed")
     return float(flops.value)
+
+
+ISSUE_PROBE_VARIANTS = ["4 matrix instructions", "each + one 2^x", "each + the work of one softmax score (no dot product)",
+                        "that + one 2-element dot product", "each + one 2-element dot product only",
+                        "pipelined turn: LDS read, 1 matrix instruction, staged softmax of 1 score",
+                        "pipelined turn: LDS read, 2 matrix instructions, staged softmax of 2 scores"]
+
+
+def pod_attn_probe_issue(variant: int, iters: int, wgs_per_unit: int, sink: int, stream: int = 0) -> float:
+    """Enqueue one instruction-mix probe; returns the matrix instructions one wavefront issues."""
+    n = ctypes.c_double(0.0)
+    status = lib().pod_attn_probe_issue(variant, iters, wgs_per_unit, ctypes.c_void_p(sink), ctypes.byref(n),
+                                        ctypes.c_void_p(stream))
+    if status != POD_OK:
+        raise PodError(status, "pod_attn_probe_issue failed")
+    return float(n.value)
 
 
 def pod_attn_probe_colocation(variant: int, a: int, b: int, c: int, bytes_per_item: int, n_memory_items: int,
