@@ -35,9 +35,9 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
-    (2, 0): 4406250906,     # 2140618.5 KiB fetched, 21742.4 KiB written
-    (3, 0): 4993570816,     # 2417705.6 KiB fetched, 41122.8 KiB written
-    (4, 0): 2595136410,     # 1247175.0 KiB fetched, 39962.9 KiB written
+    (2, 0): 4406516736,     # 2140747.1 KiB fetched, 21744.8 KiB written
+    (3, 0): 4993468826,     # 2417664.2 KiB fetched, 41106.0 KiB written
+    (4, 0): 2608362906,     # 1253646.6 KiB fetched, 39936.2 KiB written
 }
 
 
@@ -225,7 +225,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     # --- timing: every mode the same way (exactly `steps` calls bracketed by synchronisation), ----
     # --- plus per-call HIP-event times on the launch stream for the spread ------------------------
     results = {}
-    for name in ("fused", "serial", "streams", "prefill_only", "decode_only"):
+    for name in ("fused", "serial", "streams", "prefill_only", "decode_only", "fused_cta"):
         f = fwd(pod.MODES[name])
         wall = wall_us_per_step(f, steps, warmup, torch)
         ev = event_times_us(f, steps, torch)
@@ -236,7 +236,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     rec = {
         "workload": batch.name, "config": config, "batch_index": batch_index,
         "fused_us": results["fused"]["wall_us"], "serial_us": results["serial"]["wall_us"],
-        "streams_us": results["streams"]["wall_us"],
+        "streams_us": results["streams"]["wall_us"], "fused_cta_parallel_us": results["fused_cta"]["wall_us"],
         "overlap_roofline_us": t_roof_us, "bound": bound,
         "pct_of_overlap_roofline": 100.0 * t_roof_us / value_us,
         "frac": t_roof_us / value_us,
@@ -520,7 +520,8 @@ def main():
                                          "speedup_vs_streams", "max_abs_err_vs_oracle")}
                 r.update(workload=rec["config"]["workload"], config=c, batch_index=i,
                          fused_us=rec["modes"]["fused"]["wall_us"], serial_us=rec["modes"]["serial"]["wall_us"],
-                         streams_us=rec["modes"]["streams"]["wall_us"], frac=rec["pct_of_overlap_roofline"] / 100.0,
+                         streams_us=rec["modes"]["streams"]["wall_us"],
+                         fused_cta_parallel_us=rec["modes"]["fused_cta"]["wall_us"], frac=rec["pct_of_overlap_roofline"] / 100.0,
                          bound=rec["roofline"]["bound"], headline=True)
             else:
                 torch.cuda.empty_cache()

@@ -65,6 +65,13 @@ typedef enum {
  * work was split are then not written to `out`. */
 #define POD_MODE_FLAG_NO_COMBINE 0x100
 
+/* May be OR-ed into POD_MODE_FUSED: launch the fused kernel CTA-parallel, as Section 4.1 prints it
+ * (one workgroup per prefill item or per four decode units; each takes its unit's ticket, picks
+ * its operation, claims one work id, runs it and leaves), instead of as one resident round of
+ * persistent workgroups (Section 4.4's variant, the default).  Same result bit for bit; exists so
+ * that the two launch styles can be timed against each other. */
+#define POD_MODE_FLAG_CTA_PARALLEL 0x200
+
 /* Which operation a workgroup takes first on its compute unit (Section 4.1, the two policies). */
 typedef enum {
     POD_POLICY_AUTO = 0,        /* proportional, but never more decode than prefill workgroups at the
@@ -146,9 +153,8 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
 /*
  * Optional execution trace, the evidence for co-location (Section 4.1 wants both operations
  * resident on every multiprocessor).  `trace` is device memory of at least 48 bytes per workgroup
- * of the largest launch (the larger of pod_attn_plan_info.fused_grid and n_prefill_items plus the
- * decode workgroups of the stand-alone kernel, of which there are at most n_compute_units and at
- * most (n_decode_units + 3) / 4), or NULL to switch tracing off.  After a forward
+ * of the largest launch (the larger of pod_attn_plan_info.fused_grid and n_prefill_items +
+ * (n_decode_units + 3) / 4, the grid of the CTA-parallel launch), or NULL to switch tracing off.  After a forward
  * call, record w of the fused launch holds int32 {hardware unit id, first operation (0 prefill /
  * 1 decode), work items done in the first operation, work items done after switching} followed by
  * three uint64 device timestamps (100 MHz): begin, switch of operation, end, and 8 bytes of

@@ -104,6 +104,8 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     // operation the workgroups start with.
     a.dq_begin = (const int32_t *)(ws + p.off_dq);
     a.n_static_seats = p.n_static_seats;
+    a.n_dctas = ((int)p.dunits.size() + pod::kWavesPerWg - 1) / pod::kWavesPerWg;
+    a.single_unit = 0;
     a.n_combine = (int)p.centries.size();
     a.n_prefill_rows = (int)p.n_prefill_rows;
     a.p_ratio = p.p_ratio;
@@ -205,7 +207,8 @@ pod_status pod_attn_plan_set_trace(pod_attn_plan *plan, void *trace, size_t trac
 {
     if (!plan) return fail(POD_ERR_INVALID_ARG, "plan is null");
     // one record per workgroup of the largest launch: the two stand-alone kernels together, or the fused round
-    const size_t n_records = std::max(plan->p.pitems.size() + (size_t)plan->p.n_dwgs, (size_t)plan->p.fused_grid);
+    const size_t n_dctas = (plan->p.dunits.size() + pod::kWavesPerWg - 1) / pod::kWavesPerWg;
+    const size_t n_records = std::max(plan->p.pitems.size() + n_dctas, (size_t)plan->p.fused_grid);
     const size_t need = n_records * sizeof(pod::TraceRecord);
     if (trace && trace_bytes < need) return fail(POD_ERR_WORKSPACE, "trace buffer too small");
     plan->p.trace = trace;
@@ -274,7 +277,10 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
     const bool paged = p.prm.block_size > 0;
     const int n_req = p.prm.n_prefill + p.prm.n_decode;
     const bool no_combine = (mode & POD_MODE_FLAG_NO_COMBINE) != 0;
-    mode &= ~POD_MODE_FLAG_NO_COMBINE;
+    const bool cta_parallel = (mode & POD_MODE_FLAG_CTA_PARALLEL) != 0;
+    mode &= ~(POD_MODE_FLAG_NO_COMBINE | POD_MODE_FLAG_CTA_PARALLEL);
+    if (cta_parallel && mode != POD_MODE_FUSED)
+        return fail(POD_ERR_INVALID_ARG, "POD_MODE_FLAG_CTA_PARALLEL goes with POD_MODE_FUSED only");
     if (mode < POD_MODE_FUSED || mode > POD_MODE_DECODE_ONLY) return fail(POD_ERR_INVALID_ARG, "unknown mode");
     if (n_req == 0) return POD_OK;
     if (!k_cache || !v_cache || !seq_meta || !out) return fail(POD_ERR_INVALID_ARG, "k_cache, v_cache, seq_meta or out is null");
@@ -335,7 +341,15 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
 
     switch (mode) {
     case POD_MODE_FUSED:
-        go(pod::kLaunchFused, a, s);
+        if (cta_parallel) {
+            // one workgroup per work item: every decode workgroup is given its four units by index
+            pod::KernelArgs c = a;
+            c.n_static_seats = c.n_dctas;
+            c.single_unit = 1;
+            go(pod::kLaunchFusedCta, c, s);
+        } else {
+            go(pod::kLaunchFused, a, s);
+        }
         go(pod::kLaunchCombine, a, s);
         break;
     case POD_MODE_SERIAL:

@@ -143,6 +143,8 @@ struct KernelArgs {
     int32_t pq_begin[kXcdQueues + 1];      // prefill queue q holds items pq_begin[q] .. pq_begin[q+1]-1
     const int32_t *dq_begin;               // [kXcdQueues + 1]: decode queue q holds units dq_begin[q] .. dq_begin[q+1]-1
     int32_t n_static_seats;                // decode seats that start with four fixed units (units 0 .. 4*seats-1)
+    int32_t n_dctas;                       // decode workgroups of the CTA-parallel launch: ceil(n_dunits / 4)
+    int32_t single_unit;                   // CTA-parallel launch: a decode wavefront runs its fixed unit and stops
     int32_t p_ratio, d_ratio;
     float scale_log2;                      // softmax_scale * log2(e)
 };

@@ -817,7 +817,9 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     constexpr uint32_t kClaimPending = 4u;         // a claim has been issued and not looked at yet
     constexpr uint32_t kExhausted = 8u;            // every queue has been found empty
     constexpr uint32_t kDone = 16u;                // the tail has finished the last unit
-    uint32_t st = kHeadInTail;
+    // In the CTA-parallel launch a wavefront runs the one unit it was given: the queues count as
+    // used up from the start, so no claim is ever issued and the worker ends with its unit.
+    uint32_t st = kHeadInTail | (a.single_unit ? kExhausted : 0u);
     uint32_t claim_v = 0;                          // lane 0: counter value returned by the claim of the current turn
     int n_iss = 0, q_mark = 0;                     // steps issued so far; their count when the last Q copy was issued
 
@@ -989,7 +991,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
         int idx0;
         if (seat < a.n_static_seats) idx0 = __builtin_amdgcn_readfirstlane(seat) * kWavesPerWg + wave;
         else idx0 = claim_resolve(claim_now());
-        if (idx0 < 0) return 0;
+        if (idx0 < 0 || idx0 >= a.n_dunits) return 0;
         set_head(load_desc(idx0));
         cu = hu;
         q_dma(cu, 0);
@@ -1239,6 +1241,56 @@ __global__ __launch_bounds__(kWgThreads, 2) void fused_kernel(KernelArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
+// CTA-parallel fused kernel: the launch of Section 4.1's listing as printed.  One workgroup per
+// work item (a prefill item, or a decode workgroup of four one-wavefront units); the hardware
+// places workgroups as slots come free.  Each one reads its hardware unit id, takes that unit's
+// ticket, picks its operation with the ticket rule, claims the next work id of that operation from
+// a global counter, switches operation if that counter has run past its limit, runs the one item
+// and leaves.  The persistent kernel above is the variant of Section 4.4; this one exists so that
+// the two can be timed against each other on this chip.
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, int LAYOUT>
+__global__ __launch_bounds__(kWgThreads, 2) void fused_cta_kernel(KernelArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[FusedLds<D>::kBytes];
+    __shared__ int bind[4];                                  // role, work id, unit id, last flag
+    WsHeader *hdr = a.hdr;
+    const uint64_t t0 = a.trace ? wall_clock64() : 0;
+    if (threadIdx.x == 0) {
+        const unsigned cu = __smid() & (kCuSlots - 1);
+        const uint32_t ticket = atomicAdd(&hdr->cu_state[cu], 1u);
+        int role = role_for_ticket(ticket, a.p_ratio, a.d_ratio, (int)cu);
+        int id = -1;
+        for (int attempt = 0; attempt < 2 && id < 0; ++attempt) {
+            const uint32_t limit = (uint32_t)(role == kPrefill ? a.n_pitems : a.n_dctas);
+            const uint32_t k = atomicAdd(&hdr->next_item[role], 1u);
+            if (k < limit) id = (int)k;
+            else role ^= 1;                                  // that operation has no work left: the other one
+        }
+        bind[0] = id < 0 ? (int)kNone : role;
+        bind[1] = id;
+        bind[2] = (int)cu;
+    }
+    __syncthreads();
+    const int role = bind[0];
+    const int id = __builtin_amdgcn_readfirstlane(bind[1]);
+    int n_done = 0;
+    if (role == kPrefill) {
+        PrefillItem it;
+        const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.pitems + 8 * (int64_t)id;
+        it.req = w[0]; it.kv_head = w[1]; it.row0 = w[2]; it.n_rows = w[3];
+        it.kv_begin = w[4]; it.kv_end = w[5]; it.prow0 = w[6]; it.split = w[7];
+        prefill_item_run<DT, D, LAYOUT>(a, it, smem);
+        n_done = 1;
+    } else if (role == kDecode) {
+        n_done = decode_worker_run<DT, D, LAYOUT>(a, smem, id, bind[2] >> 6);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && a.trace) write_trace(a, blockIdx.x, bind[2], role, n_done, 0, t0, wall_clock64());
+    finish_and_reset(hdr, &bind[3]);
+}
+
+// ------------------------------------------------------------------------------------------
 // Combine: merge split-KV partials.  With running maxima m_s (log2 domain), weight sums l_s and
 // un-normalised outputs O_s:  M = max m_s,  out = sum_s O_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
 // ------------------------------------------------------------------------------------------
@@ -1331,6 +1383,10 @@ static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t str
     case kLaunchFused:
         if (a.fused_grid > 0)
             fused_kernel<DT, D, LAYOUT><<<dim3(a.fused_grid), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    case kLaunchFusedCta:
+        if (a.n_pitems + a.n_dctas > 0)
+            fused_cta_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems + a.n_dctas), dim3(kWgThreads), 0, stream>>>(a);
         break;
     case kLaunchCombine:
         if (a.n_crows > 0) {

@@ -19,8 +19,10 @@ POD_OK = 0
 F16, BF16 = 0, 1
 MODE_FUSED, MODE_SERIAL, MODE_STREAMS, MODE_PREFILL_ONLY, MODE_DECODE_ONLY = range(5)
 MODE_FLAG_NO_COMBINE = 0x100
+MODE_FLAG_CTA_PARALLEL = 0x200
 MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
-         "prefill_only": MODE_PREFILL_ONLY, "decode_only": MODE_DECODE_ONLY}
+         "prefill_only": MODE_PREFILL_ONLY, "decode_only": MODE_DECODE_ONLY,
+         "fused_cta": MODE_FUSED | MODE_FLAG_CTA_PARALLEL}
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
 KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 

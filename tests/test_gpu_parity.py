@@ -14,7 +14,7 @@ from tests.helpers import oracle_out
 pytestmark = pytest.mark.gpu
 
 TOL = {wl.F16: 2e-3, wl.BF16: 1e-2}
-ALL_MODES = ["fused", "serial", "streams"]
+ALL_MODES = ["fused", "serial", "streams", "fused_cta"]
 
 
 def run_gpu(batch, mode="fused", **plan_kw):
@@ -181,6 +181,9 @@ def test_repeated_launches_are_bit_identical_and_counters_reset():
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
     serial = attn.forward(dev_batch, mode=pod.MODE_SERIAL)
     assert torch.equal(first.view(torch.int16), serial.view(torch.int16))
+    for _ in range(5):                                   # the CTA-parallel launch of the same plan, same counters
+        cta = attn.forward(dev_batch, mode=pod.MODES["fused_cta"])
+        assert torch.equal(first.view(torch.int16), cta.view(torch.int16))
     torch.cuda.synchronize()
     # the whole counter block at the head of the workspace: per-unit binder state, work counters,
     # per-XCD queue counters (one 128-byte line each) and the words that idle claims add zero to
@@ -283,6 +286,8 @@ def test_full_size_batches_on_sampled_rows(config, index):
     assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} on sampled rows of {batch.name}"
     serial = attn.forward(batch, mode=pod.MODE_SERIAL)
     assert torch.equal(out.view(torch.int16), serial.view(torch.int16))
+    cta = attn.forward(batch, mode=pod.MODES["fused_cta"])
+    assert torch.equal(out.view(torch.int16), cta.view(torch.int16))
     attn.close()
 
 
