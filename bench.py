@@ -33,11 +33,17 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 # command (`--config N --no-configs`), scaled by what the same counters read for a plain device copy
 # of known size; None = not measured.  These come from the files under profiles/, not from this run.
 MEASURED_TRAFFIC_BYTES = {
-    # (config, batch_index): FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
-    # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per fused launch (files under profiles/)
-    (2, 0): 4406516736,     # 2140747.1 KiB fetched, 21744.8 KiB written
-    (3, 0): 4993468826,     # 2417664.2 KiB fetched, 41106.0 KiB written
-    (4, 0): 2608362906,     # 1253646.6 KiB fetched, 39936.2 KiB written
+    # (config, batch_index): {kernel: FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
+    # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per launch}  (files under profiles/)
+    (2, 0): {"fused_kernel": 4407163290, "fused_cta_kernel": 4609443840},
+    #   fused_kernel: 2141097.2 KiB fetched, 21676.0 KiB written
+    #   fused_cta_kernel: 2239540.2 KiB fetched, 22329.6 KiB written
+    (3, 0): {"fused_kernel": 4993989018, "fused_cta_kernel": 5158550426},
+    #   fused_kernel: 2417917.5 KiB fetched, 41107.4 KiB written
+    #   fused_cta_kernel: 2498350.1 KiB fetched, 40946.7 KiB written
+    (4, 0): {"fused_kernel": 2610979840, "fused_cta_kernel": 2764604314},
+    #   fused_kernel: 1254961.4 KiB fetched, 39862.2 KiB written
+    #   fused_cta_kernel: 1329632.5 KiB fetched, 40543.9 KiB written
 }
 
 
@@ -128,8 +134,26 @@ def plan_times_us(attn, torch, pod, reps=5):
     return {"create_us": float(np.median(create)), "upload_us": float(np.median(upload))}
 
 
+CLOCK_RAMP_S = 0.08
+
+
+def ramp_clocks(fn, torch):
+    """Untimed calls for CLOCK_RAMP_S of wall time.  After the GPU has idled (here: while the host
+    runs the oracle, copies inputs or builds a plan) its clocks take 20-40 ms of work to come back
+    up; calls timed in that window measure 5-15 % slow (configuration 4: 1328 us for iterations 5-24
+    after two idle seconds, 1257 us from iteration 50 on).  This is not one of the `--warmup` steps."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < CLOCK_RAMP_S:
+        for _ in range(4):
+            fn()
+        torch.cuda.synchronize()
+
+
 def wall_us_per_step(fn, steps, warmup, torch):
-    """Mean time of exactly `steps` back-to-back calls, bracketed by synchronisation."""
+    """Mean time of exactly `steps` back-to-back calls, bracketed by synchronisation, after
+    `warmup` untimed calls (and, before those, the clock ramp above)."""
+    ramp_clocks(fn, torch)
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -140,7 +164,7 @@ def wall_us_per_step(fn, steps, warmup, torch):
     return (time.perf_counter() - t1) / steps * 1e6
 
 
-KERNEL_OF_MODE = {"fused": "fused_kernel", "serial": "prefill_kernel + decode_kernel",
+KERNEL_OF_MODE = { "serial": "prefill_kernel + decode_kernel",
                   "streams": "prefill_kernel + decode_kernel"}
 
 
@@ -263,7 +287,8 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         achieved, peak, unit = kv_bytes / (kernel_us * 1e-6) / 1e9, PEAK_HBM / 1e9, "GB/s"
     else:
         achieved, peak, unit = flops / (kernel_us * 1e-6) / 1e12, PEAK_MFMA_16BIT / 1e12, "TFLOP/s"
-    traffic = MEASURED_TRAFFIC_BYTES.get((config, batch_index)) if main_mode == "fused" else None
+    launched = {"fused": "fused_kernel", "fused_cta": "fused_cta_kernel"}.get(main_mode)
+    traffic = MEASURED_TRAFFIC_BYTES.get((config, batch_index), {}).get(launched)
     head = {
         "metric": "hybrid-batch attention us per batch (fused prefill+decode)",
         "value": value_us, "unit": "us", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -280,7 +305,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
                      "traffic": traffic,
                      "traffic_source": "rocprofv3 --pmc summaries under profiles/ (separate runs of this command), not this run",
-                     "kernel": KERNEL_OF_MODE[main_mode], "kernel_us": kernel_us,
+                     "kernel": launched or KERNEL_OF_MODE[main_mode], "kernel_us": kernel_us,
                      "algorithmic_bytes": kv_bytes, "algorithmic_flops": flops},
         # value, the roofline percentage and the speed-ups all use the same clock: exactly `steps`
         # back-to-back forward calls (combine pass included) bracketed by synchronisation
@@ -521,7 +546,8 @@ def main():
                 r.update(workload=rec["config"]["workload"], config=c, batch_index=i,
                          fused_us=rec["modes"]["fused"]["wall_us"], serial_us=rec["modes"]["serial"]["wall_us"],
                          streams_us=rec["modes"]["streams"]["wall_us"],
-                         fused_cta_parallel_us=rec["modes"]["fused_cta"]["wall_us"], frac=rec["pct_of_overlap_roofline"] / 100.0,
+                         fused_cta_parallel_us=rec["modes"]["fused_cta"]["wall_us"],
+                         frac=rec["pct_of_overlap_roofline"] / 100.0,
                          bound=rec["roofline"]["bound"], headline=True)
             else:
                 torch.cuda.empty_cache()

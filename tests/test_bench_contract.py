@@ -19,18 +19,19 @@ def test_measured_traffic_constants_match_the_committed_profiles():
     sys.path.insert(0, ROOT)
     import bench
 
-    def per_dispatch(path):
+    def per_dispatch(path, kernel):
         with open(path) as f:
             for line in f:
-                if line.startswith("pod::fused_kernel"):
+                if line.startswith("pod::" + kernel + "<"):
                     return float(line.split()[-2])
-        raise AssertionError(f"no fused_kernel line in {path}")
+        raise AssertionError(f"no {kernel} line in {path}")
 
-    for (config, index), value in bench.MEASURED_TRAFFIC_BYTES.items():
+    for (config, index), kernels in bench.MEASURED_TRAFFIC_BYTES.items():
         assert index == 0
-        fetch = per_dispatch(os.path.join(ROOT, "profiles", f"fused_kernel_fetch_size_config{config}.txt"))
-        write = per_dispatch(os.path.join(ROOT, "profiles", f"fused_kernel_write_size_config{config}.txt"))
-        assert abs(value - (fetch * 2.0 + write) * 1024) <= 2048, (config, value, fetch, write)
+        for kernel, value in kernels.items():
+            fetch = per_dispatch(os.path.join(ROOT, "profiles", f"fused_kernel_fetch_size_config{config}.txt"), kernel)
+            write = per_dispatch(os.path.join(ROOT, "profiles", f"fused_kernel_write_size_config{config}.txt"), kernel)
+            assert abs(value - (fetch * 2.0 + write) * 1024) <= 2048, (config, kernel, value, fetch, write)
 
 
 def test_trace_report_on_synthetic_records():
