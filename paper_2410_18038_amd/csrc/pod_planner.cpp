@@ -151,10 +151,10 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
         // moves the time by 1 %; finer cuts gain nothing once the ring runs on across unit
         // boundaries, and cost partial rows and claims.)
         const int64_t slots = (int64_t)n_cus * 8;
-        // The floor is 768 keys as long as that still leaves two units for every streaming wavefront
-        // (measured on batches of 16 requests at 4K-16K keys: 2-5 % faster than 512, which in turn
-        // beats 256 and 384), else 512.
-        const int64_t floor_keys = token_heads / 768 >= 2 * (int64_t)n_cus * kWavesPerWg ? 768 : 512;
+        // The floor is 768 keys as long as that still leaves a unit for every streaming wavefront
+        // (measured on batches of 16 requests at 4K-16K keys, 1.5-2.2 units per wavefront: 2-6 %
+        // faster than 512, which in turn beats 256 and 384; 1024 is slower again), else 512.
+        const int64_t floor_keys = token_heads / 768 >= (int64_t)n_cus * kWavesPerWg ? 768 : 512;
         decode_chunk = (int)std::min<int64_t>(2048, std::max<int64_t>(floor_keys, (token_heads + 2 * slots - 1) / (2 * slots)));
         decode_chunk = round_up(decode_chunk, 256);
     }
