@@ -92,8 +92,8 @@ typedef struct {
     int32_t n_prefill;          /* prefill requests (may be 0)                                   */
     int32_t n_decode;           /* decode requests (may be 0)                                    */
     int32_t n_q_heads;          /* Hq                                                            */
-    int32_t n_kv_heads;         /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16                         */
-    int32_t head_dim;           /* d: 64 or 128                                                  */
+    int32_t n_kv_heads;         /* Hkv; Hq % Hkv == 0 and Hq / Hkv <= 16 (<= 8 at head_dim 256)  */
+    int32_t head_dim;           /* d: 64, 128 or 256                                             */
     int32_t dtype;              /* pod_dtype of q, k, v and out                                  */
     float   softmax_scale;      /* multiplies Q K^T; must be > 0 (1/sqrt(d) in normal use)       */
     int32_t block_size;         /* tokens per cache block; 0 = contiguous cache                  */

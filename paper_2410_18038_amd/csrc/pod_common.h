@@ -13,9 +13,19 @@ namespace pod {
 constexpr int kWaveSize = 64;
 constexpr int kWgThreads = 256;            // 4 wavefronts per workgroup, one per SIMD
 constexpr int kWavesPerWg = 4;
-constexpr int kPrefillRows = 128;          // packed (token, head-in-group) query rows per prefill item
-constexpr int kPrefillKvTile = 64;         // keys staged in LDS per prefill step
-constexpr int kDecodeStep = 16;            // keys per decode step of one wavefront
+constexpr int kDecodeStep = 16;            // decode units are cut at multiples of this many keys
+// Shape of a prefill work item by head dimension.  Up to 128 channels a wavefront owns 32 packed
+// (token, head-in-group) query rows and all output channels, a workgroup 128 rows, and K/V tiles
+// hold 64 keys.  At 256 channels the accumulators and queries of 32 rows no longer fit a
+// wavefront that shares its SIMD with another one, so two wavefronts share a row group: both
+// compute its scores, each owns half of the output channels; a workgroup then covers 64 rows, and
+// tiles hold 32 keys so that the four tile buffers still take 64 KB of LDS.
+POD_HD constexpr int prefill_item_rows(int head_dim) { return head_dim == 256 ? 64 : 128; }
+POD_HD constexpr int prefill_kv_tile(int head_dim) { return head_dim == 256 ? 32 : 64; }
+// Keys per decode step of one wavefront: a step's K and V rows are one slot of the register ring
+// (head_dim / 4 registers at 16 keys), which at 256 channels is halved to keep two slots.
+POD_HD constexpr int decode_step_keys(int head_dim) { return head_dim == 256 ? 8 : 16; }
+constexpr int kMaxGroup256 = 8;            // query heads per K/V head at head_dim 256 (the decode worker's query buffers)
 constexpr int kMaxGroup = 16;              // query heads per K/V head a decode unit can hold
 constexpr int kXcdQueues = 8;               // work is queued per XCD (one L2 each); a queue's counter is claimed mostly from its own XCD
 constexpr int kSlotsPerUnit = 2;            // resident workgroups per compute unit (register and LDS budget)

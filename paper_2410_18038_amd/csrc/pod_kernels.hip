@@ -202,18 +202,18 @@ __device__ __forceinline__ u32x4 load16_stream(const void *p) { return __builtin
 // ------------------------------------------------------------------------------------------
 template <int D> struct PrefillLds {
     static constexpr int kRowBytes = D * 2;
-    static constexpr int kTileBytes = kPrefillKvTile * kRowBytes;
+    static constexpr int kTileBytes = prefill_kv_tile(D) * kRowBytes;
     static constexpr int kBytes = 4 * kTileBytes;          // K[2] then V[2]
 };
 
 // Which chunk position of its LDS row a 16-byte chunk c of row `row` is stored at.
 template <int D> __device__ __forceinline__ int k_swizzle(int row, int c)
 {
-    return D == 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
+    return D >= 128 ? (c ^ (row & 15)) : (c ^ ((row >> 1) & 7));
 }
 template <int D> __device__ __forceinline__ int v_swizzle(int row, int c)
 {
-    return D == 128 ? (c ^ ((row & 3) << 2)) : (c ^ (((row >> 1) & 1) << 2));
+    return D >= 128 ? (c ^ ((row & 3) << 2)) : (c ^ (((row >> 1) & 1) << 2));
 }
 
 // 16 bytes per lane from global memory straight into LDS: lane i of the wavefront lands at
@@ -240,16 +240,20 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     using v8 = typename N::v8;
     using L = PrefillLds<D>;
     constexpr int KS = D / 16;                     // 16-channel slices of the QK^T contraction
-    constexpr int MB = D / 32;                     // 32-channel blocks of the output
+    constexpr int WPG = D == 256 ? 2 : 1;          // wavefronts per 32-row group: each owns D / WPG output channels
+    constexpr int MB = D / 32 / WPG;               // 32-channel blocks of the output owned by this wavefront
     constexpr int CH = D / 8;                      // 16-byte chunks per K/V row
-    constexpr int RPW = kWaveSize / CH;            // rows one wavefront loads per pass (4 or 8)
+    constexpr int RPW = kWaveSize / CH;            // rows one wavefront loads per pass (2, 4 or 8)
     constexpr int RPP = RPW * kWavesPerWg;         // rows per pass of the workgroup
-    constexpr int NPASS = kPrefillKvTile / RPP;
-    constexpr int T = kPrefillKvTile;
+    constexpr int T = prefill_kv_tile(D);          // keys per staged tile
+    constexpr int NTB = T / 32;                    // 32-key blocks per tile
+    constexpr int NPASS = T / RPP;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rg = wave / WPG;                     // row group of this wavefront
+    const int cb0 = (wave % WPG) * MB;             // its first 32-channel output block
     const int n32 = lane & 31;                     // query column owned by this lane
     const int h = lane >> 5;                       // which half of the contraction slots
     const int i16 = lane & 15;
@@ -263,14 +267,14 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     const int rows_total = q_len * group;
 
     // This lane's query row.
-    const int R = it.row0 + wave * 32 + n32;
-    const bool row_ok = R < rows_total && (wave * 32 + n32) < it.n_rows;
+    const int R = it.row0 + rg * 32 + n32;
+    const bool row_ok = R < rows_total && (rg * 32 + n32) < it.n_rows;
     const int tok = R / group;
     const int hq = it.kv_head * group + (R - tok * group);
     const int pos = row_ok ? prefix + tok : 0x7fffffff;    // last visible key
     // Causal limits of this wavefront (rows are ordered by token).
-    const int w_first = it.row0 + wave * 32;
-    const int w_last = min(it.row0 + it.n_rows, it.row0 + wave * 32 + 32) - 1;
+    const int w_first = it.row0 + rg * 32;
+    const int w_last = min(it.row0 + it.n_rows, it.row0 + rg * 32 + 32) - 1;
     const bool wave_has_rows = w_first < it.row0 + it.n_rows;
     const int wave_minpos = prefix + w_first / group;
     const int wave_maxpos = wave_has_rows ? prefix + w_last / group : -1;
@@ -304,7 +308,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         const int c = b16 * 2 + ((i16 & 3) >> 1);
         v_rd0 = (uint32_t)(row * L::kRowBytes + v_swizzle<D>(row, c) * 16 + (i16 & 1) * 8);
     }
-    static_assert((D == 128 || D == 64) && KS * 32 <= L::kRowBytes && MB * 64 <= L::kRowBytes, "swizzle algebra");
+    static_assert((D == 256 || D == 128 || D == 64) && KS * 32 <= L::kRowBytes && WPG * MB * 64 <= L::kRowBytes, "swizzle algebra");
     // writers: this lane's LDS chunk in pass p is row p*RPP + wave*RPW + lane/CH, position lane%CH.
     // Lane offsets (bytes) of the source chunk for full tiles.  Contiguous cache: relative to the
     // tile's first row.  Paged cache: relative to the first row of this wavefront's rows in the
@@ -446,7 +450,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 
     // S^T = K Q^T for one tile: rows = keys, columns = this wavefront's query rows.
     // Register r of block tb holds key j0 + tb*32 + 8*(r/4) + 4*h + r%4.
-    auto scores = [&](int kbuf, f32x16 (&s)[2]) {
+    auto scores = [&](int kbuf, f32x16 (&s)[NTB]) {
         const POD_LDS unsigned char *kb = lds + kbuf * L::kTileBytes;
         uint32_t k_base = k_rd0;
         asm("" : "+v"(k_base));                   // opaque copy: the XORs below stay inside the loop
@@ -454,7 +458,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         // three operations ahead of the matrix instructions that use them: inlined into the fused
         // kernel this block is otherwise emitted read-wait-multiply, sixteen times, and every
         // matrix instruction waits a full LDS latency.  0x100 = LDS read, 0x008 = matrix op.
-        constexpr int kAhead = 3, kOps = 2 * KS;
+        constexpr int kAhead = 3, kOps = NTB * KS;
         auto k_frag = [&](int i) __attribute__((always_inline)) {
             return *(const POD_LDS v8 *)(kb + (i / KS) * 32 * L::kRowBytes + (k_base ^ (uint32_t)((i % KS) << 5)));
         };
@@ -462,7 +466,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) kk[i] = k_frag(i);
 #pragma unroll
-        for (int tb = 0; tb < 2; ++tb)
+        for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[tb][r] = 0.f;
 #pragma unroll
@@ -503,11 +507,11 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // Two score buffers swap roles from one tile to the next; the loop body exists twice (even
     // and odd tiles) so that the swap is a matter of names, not of 32 register moves per tile, and
     // the LDS buffer of a tile is known at compile time.
-    f32x16 s_even[2], s_odd[2];
+    f32x16 s_even[NTB], s_odd[NTB];
     if (it.kv_begin <= wave_maxpos) scores(0, s_even);
     __syncthreads();                                         // K tile 0 is free to be overwritten
 
-    auto tile_step = [&](const int jt, auto parity, f32x16 (&s_cur)[2], f32x16 (&s_next)[2])
+    auto tile_step = [&](const int jt, auto parity, f32x16 (&s_cur)[NTB], f32x16 (&s_next)[NTB])
                          __attribute__((always_inline)) {
         const int j0 = it.kv_begin + jt * T;
         constexpr int cur = decltype(parity)::value;
@@ -537,7 +541,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
             if (__builtin_expect(need_mask, 0)) {
                 const int lim = min(pos, it.kv_end - 1);
 #pragma unroll
-                for (int tb = 0; tb < 2; ++tb)
+                for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = j0 + tb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
@@ -546,7 +550,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
             }
             float mx = neg_inf();
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+            for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s_cur[tb][r]);
             mx = max_across_32(mx) * c;
@@ -561,28 +565,28 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                     for (int r = 0; r < 16; ++r) o[mb][r] *= alpha;
             }
             const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
-            v8 pk[2][2];
+            v8 pk[NTB][2];
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+            for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r)
                     pk[tb][r >> 3][r & 7] = (typename N::elem)fast_exp2(__builtin_fmaf(s_cur[tb][r], c, -m_use));
             // the weight sum is taken over the rounded weights, the ones the PV product uses
 #pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
+            for (int tb = 0; tb < NTB; ++tb)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) l_run = N::add_all(pk[tb][u], l_run);
             // O^T += V^T P^T : rows = channels, contraction over the keys in S's own register order.
             const POD_LDS unsigned char *vb = lds + (2 + cur) * L::kTileBytes;
             uint32_t v_base = v_rd0;
             asm("" : "+v"(v_base));               // as for K above
-            // Operation j = (channel block j / 4, key block (j / 2) % 2, half j % 2); its V fragment is
-            // two transposing reads.  As for K, the reads are written and pinned two operations
-            // ahead of the matrix instruction that uses them.
-            constexpr int kAheadV = 2, kOpsV = 4 * MB;
+            // Operation j = (channel block j / (2 NTB), key block (j / 2) % NTB, half j % 2); its V
+            // fragment is two transposing reads.  As for K, the reads are written and pinned two
+            // operations ahead of the matrix instruction that uses them.
+            constexpr int kAheadV = 2, kOpsV = 2 * NTB * MB;
             auto v_frag = [&](int j) __attribute__((always_inline)) {
-                const POD_LDS unsigned char *vp = vb + (((j >> 1) & 1) * 32 + 16 * (j & 1)) * L::kRowBytes +
-                                                  (v_base ^ (uint32_t)((j >> 2) << 6));
+                const POD_LDS unsigned char *vp = vb + (((j >> 1) % NTB) * 32 + 16 * (j & 1)) * L::kRowBytes +
+                                                  (v_base ^ (uint32_t)((cb0 + j / (2 * NTB)) << 6));
                 const s16x4 lo = lds_read_tr(vp);
                 const s16x4 hi = lds_read_tr(vp + 8 * L::kRowBytes);
                 return __builtin_bit_cast(v8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -593,7 +597,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 #pragma unroll
             for (int j = 0; j < kOpsV; ++j) {
                 if (j + kAheadV < kOpsV) vv[j + kAheadV] = v_frag(j + kAheadV);
-                o[j >> 2] = N::mfma32(vv[j], pk[(j >> 1) & 1][j & 1], o[j >> 2]);
+                o[j / (2 * NTB)] = N::mfma32(vv[j], pk[(j >> 1) % NTB][j & 1], o[j / (2 * NTB)]);
             }
             __builtin_amdgcn_sched_group_barrier(0x100, 2 * kAheadV, 0);
 #pragma unroll
@@ -612,7 +616,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         tile_step(jt + 1, std::integral_constant<int, 1>{}, s_odd, s_even);
     }
 
-    // Epilogue.  o[mb][r] is channel mb*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
+    // Epilogue.  o[mb][r] is channel (cb0 + mb)*32 + 8*(r/4) + 4*h + r%4 of this lane's query row.
     const float l_tot = sum_across_32(l_run);
     if (it.prow0 < 0) {
         if (row_ok) {
@@ -626,20 +630,20 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
                     typename N::v4 w;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) w[e] = (typename N::elem)(o[mb][rq * 4 + e] * inv);
-                    *(typename N::v4 *)(op + mb * 32 + 8 * rq + 4 * h) = w;
+                    *(typename N::v4 *)(op + (cb0 + mb) * 32 + 8 * rq + 4 * h) = w;
                 }
         }
     } else {
-        const int64_t prow = (int64_t)it.prow0 + wave * 32 + n32;
+        const int64_t prow = (int64_t)it.prow0 + rg * 32 + n32;
         float *po = a.part_o + prow * D;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 f32x4 w = {o[mb][rq * 4 + 0], o[mb][rq * 4 + 1], o[mb][rq * 4 + 2], o[mb][rq * 4 + 3]};
-                *(f32x4 *)(po + mb * 32 + 8 * rq + 4 * h) = w;
+                *(f32x4 *)(po + (cb0 + mb) * 32 + 8 * rq + 4 * h) = w;
             }
-        if (h == 0) {
+        if (h == 0 && cb0 == 0) {
             a.part_ml[prow * 2 + 0] = m_run;
             a.part_ml[prow * 2 + 1] = l_tot;
         }
@@ -660,11 +664,17 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
 // few percent of the time only (Section 4.2.1).
 // ------------------------------------------------------------------------------------------
 template <int D> struct DecodeLds {
+    static constexpr int kStep = decode_step_keys(D);          // keys per step
     static constexpr int kKStride = D * 2 + 16;
     static constexpr int kVStride = D * 2 + 32;
-    static constexpr int kKBytes = kDecodeStep * kKStride;
-    static constexpr int kVBytes = kDecodeStep * kVStride;
-    static constexpr int kQSlice = kWaveSize * 16;             // one 16-byte piece per lane
+    static constexpr int kKBytes = kStep * kKStride;
+    static constexpr int kVBytes = kStep * kVStride;
+    // Query heads of a unit as MFMA operands: per 32-channel slice one 16-byte piece for each of 4
+    // channel groups x kQCols columns (heads of the group).  Up to 128 channels every lane of the
+    // wavefront has a piece (16 columns, zero padded); at 256 channels the group is at most 8 heads
+    // and only those 8 columns are stored, which halves the buffers.
+    static constexpr int kQCols = D == 256 ? kMaxGroup256 : 16;
+    static constexpr int kQSlice = 4 * kQCols * 16;
     static constexpr int kQBuf = (D / 32) * kQSlice;           // one unit's query heads as MFMA operands
     static constexpr int kQBytes = 2 * kQBuf;                  // the tail's unit and the unit fetched ahead
     static constexpr int kBytesPerWave = kKBytes + kVBytes + kQBytes;
@@ -680,7 +690,7 @@ template <int D, int LAYOUT> struct DecodeRing {
     // same) and for the prefill role running beside it (its tile loads wait in the same queues).
     // The price: a wavefront alone on the chip streams 10.7 instead of 12.8 GB/s.  The any-block-size layout looks up block ids with vector loads before each
     // step and gets one more slot to cover them; D = 64 slots are half the size.
-    static constexpr int kDepth = D == 128 ? (LAYOUT == kLayoutPagedAny ? 3 : 2) : 4;
+    static constexpr int kDepth = D >= 128 ? (LAYOUT == kLayoutPagedAny ? 3 : 2) : 4;
 };
 
 // Placed right after a branch on a per-lane condition inside code that keeps wavefront-uniform
@@ -711,7 +721,9 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     constexpr int MB = D / 16;                     // 16-channel blocks of the output
     constexpr int CH = D / 8;                      // 16-byte chunks per row
     constexpr int RPI = kWaveSize / CH;            // rows per load instruction
-    constexpr int NLD = kDecodeStep / RPI;         // load instructions per step, for K and for V
+    constexpr int STEP = L::kStep;                 // keys per step (16; 8 at 256 channels)
+    constexpr int NLD = STEP / RPI;                // load instructions per step, for K and for V
+    constexpr int QC = L::kQCols;                  // query columns held in LDS
     constexpr int R = DecodeRing<D, LAYOUT>::kDepth;
     constexpr int kDummy = 0x3fffffff;             // slot holds no step (all its keys are masked)
     constexpr int kClaimAhead = 2 * R;             // the head claims its next unit this many steps before it runs out
@@ -779,7 +791,14 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     // turn) and moved to registers when the tail enters the unit.  Lanes of columns beyond the
     // group read zeros written once.
     int q_cur = 0;                                 // buffer of the tail's unit
-    if (!col_ok) {
+    // A direct-to-LDS load puts lane i's piece at position i of the slice, so the lane that copies
+    // piece (column, channel group) is the lane whose number is that piece's position: every lane
+    // with 16 columns (position = channel group * 16 + column), lanes 0..31 with 8 columns
+    // (position = channel group * 8 + column).
+    const int cp_col = QC == 16 ? n16 : (lane & 7), cp_b4 = QC == 16 ? b4 : (lane >> 3);
+    const bool cp_slot = QC == 16 || lane < 4 * QC;           // this lane has a position in a slice
+    const bool cp_ok = cp_slot && cp_col < group;             // ... and a query head to copy there
+    if (cp_slot && !cp_ok) {
 #pragma unroll
         for (int i = 0; i < 2 * KS; ++i) *(POD_LDS u32x4 *)(lds_q + i * L::kQSlice + lane * 16) = u32x4{0u, 0u, 0u, 0u};
     }
@@ -787,19 +806,27 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     auto q_dma = [&](const Desc &d, int buf) __attribute__((always_inline)) {
         const char *qb = (const char *)((const elem *)a.decode_q +
                                         ((int64_t)d.q_start * a.n_q_heads + d.kv_head * group) * D);
-        const uint32_t vo = (uint32_t)(n16 * D + b4 * 8) * 2u;
+        const uint32_t vo = (uint32_t)(cp_col * D + cp_b4 * 8) * 2u;
         const uint32_t dst = (uint32_t)(uintptr_t)lds_q + (uint32_t)(buf * L::kQBuf);
-        if (col_ok) {
+        if (cp_ok) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) dma16_vaddr(dst + ks * L::kQSlice, qb + vo + ks * 64);
         }
         lane_test_done();
     };
     v8 q[KS];
+    const int q_piece = QC == 16 ? lane : b4 * QC + (n16 & (QC - 1));   // this lane's piece of a slice as an MFMA operand
     auto q_from_lds = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            q[ks] = *(const POD_LDS v8 *)(lds_q + q_cur * L::kQBuf + ks * L::kQSlice + lane * 16);
+        for (int ks = 0; ks < KS; ++ks) {
+            q[ks] = *(const POD_LDS v8 *)(lds_q + q_cur * L::kQBuf + ks * L::kQSlice + q_piece * 16);
+            if constexpr (QC < 16) {
+                // columns beyond the stored ones are zero
+                const u32x4 raw = __builtin_bit_cast(u32x4, q[ks]);
+                const u32x4 zero = {0u, 0u, 0u, 0u};
+                q[ks] = __builtin_bit_cast(v8, n16 < QC ? raw : zero);
+            }
+        }
     };
 
     // ---- head: the step whose rows are requested next ----------------------------------------
@@ -826,7 +853,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     // Rows past the end of a unit's last step re-read its last row (the keys are masked out of the
     // softmax by index), so every load is in bounds and none sits behind a branch.
     auto set_voff = [&](int t_first, int t1) __attribute__((always_inline)) {
-        const int last_row = min(t1 - 1 - t_first, kDecodeStep - 1);
+        const int last_row = min(t1 - 1 - t_first, STEP - 1);
 #pragma unroll
         for (int p = 0; p < NLD; ++p) {
             const int row = min(p * RPI + ld_row, last_row);
@@ -883,12 +910,12 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
     };
     auto advance_head = [&]() __attribute__((always_inline)) {
         if (h_t < hu.t1) {
-            h_t += kDecodeStep;
+            h_t += STEP;
             if (h_t < hu.t1) {
                 h_addr_t = h_t;
-                if constexpr (LAYOUT == kLayoutContiguous) h_base += (int64_t)kDecodeStep * token_elems;
+                if constexpr (LAYOUT == kLayoutContiguous) h_base += (int64_t)STEP * token_elems;
                 else h_base = base_of(hu.cache_row, h_t);
-                if (h_t + kDecodeStep > hu.t1) set_voff(h_t, hu.t1);     // ragged last step
+                if (h_t + STEP > hu.t1) set_voff(h_t, hu.t1);     // ragged last step
             }
         }
     };
@@ -921,14 +948,15 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
             *(POD_LDS u32x4 *)(lds_v + row * L::kVStride + ld_chunk * 16) = sl.v[p];
         }
         wave_lds_sync();                           // rows written by some lanes are read by others
-        // S^T tile: register r holds key t_first + 4*b4 + r of query column n16.
+        // S^T tile: register r holds key t_first + 4*b4 + r of query column n16.  (With 8-key steps
+        // the matrix rows 8..15 repeat rows 0..7 and are masked like keys past the unit's end.)
         f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            const v8 kk = *(const POD_LDS v8 *)(lds_k + n16 * L::kKStride + (ks * 32 + b4 * 8) * 2);
+            const v8 kk = *(const POD_LDS v8 *)(lds_k + (n16 & (STEP - 1)) * L::kKStride + (ks * 32 + b4 * 8) * 2);
             s = N::mfma16(kk, q[ks], s);
         }
-        const int n_valid = cu.t1 - t_first - 4 * b4;         // keys of this lane that exist
+        const int n_valid = min(cu.t1 - t_first, STEP) - 4 * b4;         // keys of this lane that exist
 #pragma unroll
         for (int r = 0; r < 4; ++r) s[r] = (r < n_valid) ? s[r] : neg_inf();
         float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
@@ -952,7 +980,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
         // O^T += V^T P^T over these 16 keys: lane's contraction slots 4*b4 + r are keys 4*b4 + r.
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb) {
-            const POD_LDS unsigned char *vp = lds_v + (4 * b4 + (n16 >> 2)) * L::kVStride +
+            const POD_LDS unsigned char *vp = lds_v + ((4 * b4 + (n16 >> 2)) & (STEP - 1)) * L::kVStride +
                                       (mb * 16 + (n16 & 3) * 4) * 2;
             o[mb] = N::mfma16k16(lds_read_tr(vp), pk, o[mb]);
         }
@@ -1022,7 +1050,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
                 // Claim ahead, once the head is close to the end of its unit: the answer is picked
                 // up at the end of this turn, by when the slot requested right after the claim
                 // has been waited for, and memory operations return in issue order.
-                const bool want = st == kHeadInTail && hu.t1 - h_t <= kClaimAhead * kDecodeStep;
+                const bool want = st == kHeadInTail && hu.t1 - h_t <= kClaimAhead * STEP;
                 st |= want ? kClaimPending : 0u;
                 uint32_t *ctr = want ? &a.hdr->next_dunit_xcd[cq][0] : null_ctr;
                 if (lane == 0) claim_v = atomicAdd(ctr, want ? 1u : 0u);
@@ -1040,7 +1068,7 @@ __device__ __forceinline__ int decode_worker_run(const KernelArgs &a, unsigned c
             const int t_first = slot_t[r];
             consume(ring[r], t_first);
             __builtin_amdgcn_sched_barrier(0);
-            if (t_first != kDummy && t_first + kDecodeStep >= cu.t1) {
+            if (t_first != kDummy && t_first + STEP >= cu.t1) {
                 // last step of the tail's unit
                 finish_unit(cu);
                 if (a.evlog) {
@@ -1420,6 +1448,8 @@ hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool 
     if (dtype == 0 && head_dim == 64) return launch_layout<0, 64>(which, a, layout, stream);
     if (dtype == 1 && head_dim == 128) return launch_layout<1, 128>(which, a, layout, stream);
     if (dtype == 1 && head_dim == 64) return launch_layout<1, 64>(which, a, layout, stream);
+    if (dtype == 0 && head_dim == 256) return launch_layout<0, 256>(which, a, layout, stream);
+    if (dtype == 1 && head_dim == 256) return launch_layout<1, 256>(which, a, layout, stream);
     return hipErrorInvalidValue;
 }
 

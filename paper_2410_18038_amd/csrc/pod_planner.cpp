@@ -54,7 +54,8 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     }
     const int group = prm.n_q_heads / prm.n_kv_heads;
     if (group > kMaxGroup) { err = "more than 16 query heads per K/V head"; return POD_ERR_UNSUPPORTED; }
-    if (prm.head_dim != 64 && prm.head_dim != 128) { err = "head_dim must be 64 or 128"; return POD_ERR_UNSUPPORTED; }
+    if (prm.head_dim != 64 && prm.head_dim != 128 && prm.head_dim != 256) { err = "head_dim must be 64, 128 or 256"; return POD_ERR_UNSUPPORTED; }
+    if (prm.head_dim == 256 && group > kMaxGroup256) { err = "head_dim 256: more than 8 query heads per K/V head"; return POD_ERR_UNSUPPORTED; }
     if (prm.dtype != POD_F16 && prm.dtype != POD_BF16) { err = "dtype must be POD_F16 or POD_BF16"; return POD_ERR_UNSUPPORTED; }
     if (!(prm.softmax_scale > 0.f) || !std::isfinite(prm.softmax_scale)) {
         err = "softmax_scale must be positive and finite";
@@ -169,6 +170,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     // Row blocks of 128 packed rows per K/V head; split-KV only when there are too few blocks to
     // fill the chip, and never beyond `max_prefill_waves` chip-wide rounds (Section 4.2.4).
     {
+        const int kPrefillRows = prefill_item_rows(prm.head_dim), kPrefillKvTile = prefill_kv_tile(prm.head_dim);
         int64_t base_items = 0;
         for (int r = 0; r < prm.n_prefill; ++r)
             base_items += (int64_t)prm.n_kv_heads * ceil_div(seq_meta[4 * r + 1] * group, kPrefillRows);

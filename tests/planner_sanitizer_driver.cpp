@@ -50,7 +50,7 @@ bool check_plan(const pod_attn_params &prm, const std::vector<int32_t> &meta, co
         CHECK(it.row0 >= 0 && it.n_rows > 0 && it.row0 + it.n_rows <= q_len * group, "rows %d+%d", it.row0, it.n_rows);
         CHECK(it.kv_begin >= 0 && it.kv_begin < it.kv_end && it.kv_end <= kv_len, "keys %d..%d of %d", it.kv_begin,
               it.kv_end, kv_len);
-        CHECK(it.prow0 == -1 || (it.prow0 >= 0 && it.prow0 + pod::kPrefillRows <= p.n_partial_rows), "partial row %d",
+        CHECK(it.prow0 == -1 || (it.prow0 >= 0 && it.prow0 + pod::prefill_item_rows(prm.head_dim) <= p.n_partial_rows), "partial row %d",
               it.prow0);
         cover[{it.req, {it.kv_head, it.row0}}].push_back({it.kv_begin, it.kv_end});
     }
@@ -59,7 +59,7 @@ bool check_plan(const pod_attn_params &prm, const std::vector<int32_t> &meta, co
         std::sort(v.begin(), v.end());
         const int r = kv.first.first, row0 = kv.first.second.second;
         const int q_len = meta[4 * r + 1], kv_len = meta[4 * r + 2];
-        const int n_rows = std::min(pod::kPrefillRows, q_len * group - row0);
+        const int n_rows = std::min(pod::prefill_item_rows(prm.head_dim), q_len * group - row0);
         const int kmax = kv_len - q_len + (row0 + n_rows - 1) / group + 1;
         CHECK(v.front().first == 0 && v.back().second == kmax, "cover %d..%d of %d", v.front().first, v.back().second, kmax);
         for (size_t i = 1; i < v.size(); ++i) CHECK(v[i].first == v[i - 1].second, "gap at %d", v[i].first);
@@ -121,7 +121,7 @@ int main(int argc, char **argv)
         const int group = one_of({1, 2, 4, 8, 16});
         prm.n_kv_heads = hkv;
         prm.n_q_heads = hkv * group;
-        prm.head_dim = one_of({64, 128});
+        prm.head_dim = group <= 8 ? one_of({64, 128, 256}) : one_of({64, 128});   // 256 channels: at most 8 heads per K/V head
         prm.dtype = pick(0, 1);
         prm.softmax_scale = 0.1f;
         prm.n_prefill = pick(0, 3);

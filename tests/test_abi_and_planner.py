@@ -89,6 +89,7 @@ def test_invalid_arguments_are_rejected_with_a_message():
 
     expect(-1, params_for(b, n_kv_heads=3))
     expect(-2, params_for(b, head_dim=96))
+    expect(-2, params_for(b, head_dim=256, n_q_heads=64, n_kv_heads=4))        # 16 query heads per K/V head at 256 channels
     expect(-2, params_for(b, dtype=5))
     expect(-2, params_for(b, n_q_heads=32, n_kv_heads=1))          # 32 query heads on one K/V head
     expect(-1, params_for(b, softmax_scale=0.0))
@@ -148,17 +149,18 @@ def coverage_check(prm, meta):
     assert info.fused_grid == (2 * info.n_compute_units if full_round
                                else min(2 * info.n_compute_units, len(items) + n_workers))
     # prefill: per (request, kv head, row block) the key ranges tile [0, kmax) without gaps
+    item_rows, tile = (64, 32) if prm.head_dim == 256 else (128, 64)       # shape of a prefill item by head_dim
     blocks = {}
     for req, kvh, row0, n_rows, k0, k1, prow0, split in items:
-        assert row0 % 128 == 0 and 1 <= n_rows <= 128 and k0 % 64 == 0 and k0 < k1
+        assert row0 % item_rows == 0 and 1 <= n_rows <= item_rows and k0 % tile == 0 and k0 < k1
         blocks.setdefault((req, kvh, row0, n_rows), []).append((k0, k1, prow0, split))
     want_blocks = 0
     for r in range(prm.n_prefill):
         q_len, kv_len = int(meta[r, 1]), int(meta[r, 2])
         rows = q_len * group
         for kvh in range(prm.n_kv_heads):
-            for row0 in range(0, rows, 128):
-                n_rows = min(128, rows - row0)
+            for row0 in range(0, rows, item_rows):
+                n_rows = min(item_rows, rows - row0)
                 kmax = kv_len - q_len + (row0 + n_rows - 1) // group + 1
                 parts = sorted(blocks[(r, kvh, row0, n_rows)])
                 assert parts[0][0] == 0 and parts[-1][1] == kmax
@@ -182,7 +184,7 @@ def coverage_check(prm, meta):
             assert all((p[2] >= 0) == (len(parts) > 1) for p in parts)
     assert len(ranges) == prm.n_decode * prm.n_kv_heads
     # partial rows do not overlap
-    spans = [(p, p + 128) for *_, p, _ in [tuple(i) for i in items] if p >= 0]
+    spans = [(p, p + item_rows) for *_, p, _ in [tuple(i) for i in items] if p >= 0]
     spans += [(int(u[4]), int(u[4]) + group) for u in units if u[4] >= 0]
     spans.sort()
     for a, b in zip(spans, spans[1:]):
@@ -193,7 +195,7 @@ def coverage_check(prm, meta):
     # first inside a queue
     n_streams = prm.n_prefill * prm.n_kv_heads
     per = 8 // n_streams if 0 < n_streams < 8 else 1
-    queues = [(int(i[0] * prm.n_kv_heads + i[1]) * per + (int(i[2]) // 128) % per) % 8 for i in items]
+    queues = [(int(i[0] * prm.n_kv_heads + i[1]) * per + (int(i[2]) // item_rows) % per) % 8 for i in items]
     assert queues == sorted(queues)
     for q in set(queues):
         lens = [int(i[5] - i[4]) for i, qq in zip(items, queues) if qq == q]
@@ -302,7 +304,8 @@ def test_random_batches_and_tuning_values_plan_cleanly():
         hkv = int(rng.choice([1, 2, 3, 5, 8]))
         group = int(rng.choice([1, 2, 3, 4, 8, 16]))
         prm, meta = meta_only(f"rand{case}", prefill, decodes, hq=hkv * group, hkv=hkv,
-                              d=int(rng.choice([64, 128])), block_size=int(rng.choice([0, 16])))
+                              d=int(rng.choice([64, 128, 256])) if group <= 8 else int(rng.choice([64, 128])),
+                              block_size=int(rng.choice([0, 16])))
         prm.n_compute_units = int(rng.choice([1, 2, 7, 64, 256, 304]))
         prm.decode_chunk = int(rng.choice([0, 0, 16, 100, 256, 4096]))
         prm.prefill_split_len = int(rng.choice([0, 0, 64, 300, 1 << 20]))

@@ -65,10 +65,12 @@ def test_single_operation_modes_write_only_their_rows(mode):
 
 @pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
 @pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (8, 1), (16, 1)])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("block_size", [0, 16])
 def test_shapes_dtypes_layouts(dtype, hq, hkv, d, block_size):
     """Several tiles and ragged tails in both operations; cache tails and spare blocks poisoned."""
+    if d == 256 and hq // hkv > 8:
+        pytest.skip("head_dim 256 takes at most 8 query heads per K/V head")
     batch = wl.make_batch(f"grid-{hq}/{hkv}-d{d}-bs{block_size}", prefill=[(200, 333), (37, 37)],
                           decode_kv_lens=[1, 31, 32, 33, 257, 700], n_q_heads=hq, n_kv_heads=hkv,
                           head_dim=d, dtype=dtype, seed=1000 + hq * 7 + hkv + d + block_size,
@@ -77,7 +79,7 @@ def test_shapes_dtypes_layouts(dtype, hq, hkv, d, block_size):
 
 
 @pytest.mark.parametrize("hq,hkv", [(5, 5), (9, 3), (10, 5)])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("block_size", [0, 16, 64, 24])
 def test_token_sizes_that_are_no_power_of_two(hq, hkv, d, block_size):
     """K/V head counts of 3 and 5: a cached token of 768 ... 2560 bytes, in the contiguous layout,
@@ -90,7 +92,7 @@ def test_token_sizes_that_are_no_power_of_two(hq, hkv, d, block_size):
     check(batch, "serial", decode_chunk=256, prefill_split_len=128, max_prefill_waves=64)
 
 
-@pytest.mark.parametrize("dtype,hq,hkv,d", [(wl.F16, 8, 2, 128), (wl.BF16, 6, 3, 64), (wl.F16, 4, 4, 128)])
+@pytest.mark.parametrize("dtype,hq,hkv,d", [(wl.F16, 8, 2, 128), (wl.BF16, 6, 3, 64), (wl.F16, 4, 4, 128), (wl.BF16, 8, 2, 256)])
 @pytest.mark.parametrize("block_size", [0, 16, 32, 24])
 def test_head_major_cache(dtype, hq, hkv, d, block_size):
     """The [.., Hkv, tokens, d] cache order in every address path: contiguous, block-wise paged
@@ -105,10 +107,11 @@ def test_head_major_cache(dtype, hq, hkv, d, block_size):
 
 @pytest.mark.parametrize("mode", ALL_MODES)
 @pytest.mark.parametrize("block_size", [0, 16, 48])
-def test_split_kv_paths(mode, block_size):
+@pytest.mark.parametrize("d", [128, 256])
+def test_split_kv_paths(mode, block_size, d):
     """Force split-KV in both operations (short chunks, tiny split lengths) and merge the partials."""
-    batch = wl.make_batch(f"split-bs{block_size}", prefill=[(96, 1500)], decode_kv_lens=[1200, 90, 2047, 640],
-                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.BF16, seed=77 + block_size,
+    batch = wl.make_batch(f"split-bs{block_size}-d{d}", prefill=[(96, 1500)], decode_kv_lens=[1200, 90, 2047, 640],
+                          n_q_heads=8, n_kv_heads=2, head_dim=d, dtype=wl.BF16, seed=77 + block_size,
                           block_size=block_size, poison=float("nan"))
     err, info = check(batch, mode, decode_chunk=256, prefill_split_len=256, max_prefill_waves=64)
     assert info.max_prefill_splits > 1 and info.max_decode_splits > 1
@@ -148,7 +151,7 @@ def test_random_batches_and_tuning_values():
         group = int(rng.choice([1, 2, 4, 7, 16]))
         dtype = int(rng.choice([wl.F16, wl.BF16]))
         batch = wl.make_batch(f"rand{case}", prefill=prefill, decode_kv_lens=decodes, n_q_heads=hkv * group,
-                              n_kv_heads=hkv, head_dim=int(rng.choice([64, 128])), dtype=dtype,
+                              n_kv_heads=hkv, head_dim=int(rng.choice([64, 128, 256] if group <= 8 else [64, 128])), dtype=dtype,
                               seed=7000 + case, block_size=int(rng.choice([0, 16, 32, 40])), poison=float("nan"))
         if rng.integers(0, 2):
             batch = wl.to_head_major(batch)
@@ -163,10 +166,11 @@ def test_degenerate_batches():
     """Only prefill, only decode, one key, a chunk without prefix."""
     for name, prefill, decodes in [("only-prefill", [(65, 65)], []), ("only-decode", [], [1, 5, 64]),
                                    ("one-key", [(1, 1)], [1]), ("no-prefix", [(130, 130)], [3])]:
-        batch = wl.make_batch(name, prefill=prefill, decode_kv_lens=decodes, n_q_heads=4, n_kv_heads=2,
-                              head_dim=64, dtype=wl.F16, seed=5, poison=float("nan"))
-        for mode in ALL_MODES:
-            check(batch, mode)
+        for d in (64, 256):
+            batch = wl.make_batch(f"{name}-d{d}", prefill=prefill, decode_kv_lens=decodes, n_q_heads=4, n_kv_heads=2,
+                                  head_dim=d, dtype=wl.F16, seed=5, poison=float("nan"))
+            for mode in ALL_MODES:
+                check(batch, mode)
 
 
 def test_repeated_launches_are_bit_identical_and_counters_reset():
@@ -217,7 +221,7 @@ def test_decode_stream_crosses_many_short_units():
     are emptied and the other XCDs' queues are tried), in all three launch modes."""
     rng = np.random.Generator(np.random.PCG64(321))
     lens = rng.integers(1, 41, size=150).tolist() + [5000, 17, 3001, 1, 16, 4097]
-    for hq, hkv, d, bs in [(8, 2, 128, 16), (4, 4, 64, 0), (16, 1, 128, 48)]:
+    for hq, hkv, d, bs in [(8, 2, 128, 16), (4, 4, 64, 0), (16, 1, 128, 48), (8, 1, 256, 16)]:
         batch = wl.make_batch(f"stream-{hq}/{hkv}-d{d}-bs{bs}", prefill=[(70, 200)], decode_kv_lens=lens,
                               n_q_heads=hq, n_kv_heads=hkv, head_dim=d, dtype=wl.F16, seed=4242 + d + bs,
                               block_size=bs, poison=float("nan"))
@@ -288,6 +292,31 @@ def test_full_size_batches_on_sampled_rows(config, index):
     assert torch.equal(out.view(torch.int16), serial.view(torch.int16))
     cta = attn.forward(batch, mode=pod.MODES["fused_cta"])
     assert torch.equal(out.view(torch.int16), cta.view(torch.int16))
+    attn.close()
+
+
+def test_head_dim_256_at_benchmark_size():
+    """A batch of the size of the benchmark configurations at 256 channels per head (16 query heads on 8 K/V
+    heads, a 1024-token chunk ending at 4096 beside 64 decodes at 2K-8K keys, 16-key blocks): sampled
+    rows against the oracle, serial and CTA-parallel launches bit-identical to the fused one."""
+    rng = np.random.Generator(np.random.PCG64(256))
+    batch = wl.make_batch("d256-16/8", prefill=[(1024, 4096)], decode_kv_lens=rng.integers(2048, 8193, 64).tolist(),
+                          n_q_heads=16, n_kv_heads=8, head_dim=256, dtype=wl.BF16, seed=2560, block_size=16,
+                          device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    out = attn.forward(batch)
+    torch.cuda.synchronize()
+    rows = _sample_rows(batch, 24, 24, seed=256)
+    print(f"case {batch.name}: {len(rows)} sampled rows of {batch.n_rows}, {attn.info.n_prefill_items} items, "
+          f"{attn.info.n_decode_units} units", flush=True)
+    want = oracle_out(batch, rows=rows)
+    got = out[torch.from_numpy(rows.astype(np.int64)).to("cuda:0")].to(torch.float64).cpu().numpy()
+    assert bool(torch.isfinite(out.to(torch.float32)).all())
+    err = np.abs(got - want).max()
+    assert err <= TOL[batch.dtype], f"max-abs error {err:.3e} on sampled rows of {batch.name}"
+    for mode in ("serial", "fused_cta"):
+        other = attn.forward(batch, mode=pod.MODES[mode])
+        assert torch.equal(out.view(torch.int16), other.view(torch.int16)), mode
     attn.close()
 
 

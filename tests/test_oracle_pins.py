@@ -249,7 +249,8 @@ def test_future_keys_inside_the_chunk_are_ignored():
 
 
 # -- p11: a library routine on the same problem ------------------------------------------ #
-@pytest.mark.parametrize("dtype,hq,hkv,d", [(F16, 4, 4, 64), (BF16, 8, 2, 128), (F16, 8, 1, 32)])
+@pytest.mark.parametrize("dtype,hq,hkv,d", [(F16, 4, 4, 64), (BF16, 8, 2, 128), (F16, 8, 1, 32), (BF16, 8, 2, 256),
+                                             (F16, 4, 4, 256)])
 def test_matches_torch_sdpa_in_float64(dtype, hq, hkv, d):
     """torch's scaled_dot_product_attention in fp64 with an explicit boolean mask."""
     b = wl.make_batch("sdpa", prefill=[(40, 100), (17, 17)], decode_kv_lens=[1, 64, 77], n_q_heads=hq,
