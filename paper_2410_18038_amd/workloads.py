@@ -286,6 +286,9 @@ def config_batch(config: int, batch_index: int = 0, device="cpu",
        at context 32768.
     5: 32 q / 8 kv, d 128, bf16, paged 16; chunk in {256..2048} ending at 4096;
        {16, 64, 256} decodes with context uniform in [4096, 16384].
+    6: (an extra, not one of the benchmark configurations) 16 q / 8 kv, d 256, bf16,
+       paged 16; chunk 1024 ending at 4096; 64 decodes with context uniform in
+       [2048, 8192]: the one shape that exercises 256 channels per head.
     """
     seed = config_seed(config, batch_index)
     rng = np.random.Generator(np.random.PCG64(seed ^ 0x5EED))
@@ -309,7 +312,11 @@ def config_batch(config: int, batch_index: int = 0, device="cpu",
         lens = rng.integers(4096, 16385, size=nd).tolist()
         return make_batch(f"config5-sweep-c{chunk}-d{nd}", prefill=[(chunk, 4096)], decode_kv_lens=lens,
                           n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=BF16, block_size=16, **common)
-    raise ValueError("config must be 1..5")
+    if config == 6:
+        lens = rng.integers(2048, 8193, size=64).tolist()
+        return make_batch("extra-d256-gqa2", prefill=[(1024, 4096)], decode_kv_lens=lens, n_q_heads=16,
+                          n_kv_heads=8, head_dim=256, dtype=BF16, block_size=16, **common)
+    raise ValueError("config must be 1..6")
 
 
 # ----------------------------------------------------------------------------------------------
