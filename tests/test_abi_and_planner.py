@@ -136,6 +136,36 @@ def test_forward_rejects_missing_buffers_without_touching_the_gpu():
     plan.close()
 
 
+def test_static_scratch_entry_point_checks_sizes_before_touching_the_gpu():
+    """`pod_attn_forward_static` refuses a plan whose workspace exceeds its fixed array, and the
+    two-stream mode, with a message and without any device call (this runs without a GPU)."""
+    meta = np.zeros((512, 4), dtype=np.int32)
+    meta[:, 0] = np.arange(512)
+    meta[:, 1] = 1
+    meta[:, 2] = 16384
+    meta[:, 3] = np.arange(512)
+    prm = pod.make_params(n_prefill=0, n_decode=512, n_q_heads=32, n_kv_heads=8, head_dim=128, dtype=wl.BF16,
+                          softmax_scale=128 ** -0.5, block_size=16, max_blocks_per_seq=1024, n_cache_rows=512,
+                          n_blocks=1 << 20, decode_chunk=256, n_compute_units=256)
+    plan = pod.pod_attn_plan_create(prm, meta)
+    assert pod.pod_attn_workspace_size(plan) > pod.STATIC_SCRATCH_BYTES
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_attn_forward_static(0, 256, 256, 256, 256, 256, 256, plan)
+    assert e.value.status == -3 and str(pod.STATIC_SCRATCH_BYTES) in str(e.value)
+    plan.close()
+    b = wl.config_batch(1)
+    plan = pod.pod_attn_plan_create(params_for(b), b.seq_meta)
+    with pytest.raises(pod.PodError) as e:
+        pod.pod_attn_forward_static(256, 256, 256, 256, 256, 0, 256, plan, mode=pod.MODE_STREAMS)
+    assert e.value.status == -2
+    with pytest.raises(pod.PodError) as e:                       # null buffers are caught as in pod_attn_forward
+        pod.pod_attn_forward_static(0, 0, 0, 0, 0, 0, 0, plan)
+    assert e.value.status == -1
+    header = open(os.path.join(ROOT, "include", "pod_attn.h")).read()
+    assert "#define POD_ATTN_STATIC_SCRATCH_BYTES ((size_t)64 << 20)" in header and pod.STATIC_SCRATCH_BYTES == 64 << 20
+    plan.close()
+
+
 # -- planner: every (row, key) pair and every decode token is covered exactly once --------------- #
 def coverage_check(prm, meta):
     plan = pod.pod_attn_plan_create(prm, meta)
