@@ -73,6 +73,23 @@ typedef enum {
  * on every benchmark batch of this chip once its clocks are up). */
 #define POD_MODE_FLAG_CTA_PARALLEL 0x200
 
+/* May be OR-ed into POD_MODE_FUSED: the prefill-heavy occupancy configuration (Section 4.2.2 ships
+ * two configurations, with more or fewer resident workgroups per multiprocessor, and picks one per
+ * batch).  Instead of the one fused kernel with two workgroups per compute unit, two kernels are
+ * started together on the library's two side streams: the prefill kernel held to 208 registers
+ * and a light decode kernel of 96 registers and 16 KB of LDS, so that every compute unit holds two
+ * prefill workgroups AND one decode workgroup for the whole launch (what places them together is
+ * that nothing else fits; the trace records show where each workgroup ran).  Same result within
+ * rounding (the decode kernel adds its weights in another order).  Built for head_dim 128 and for
+ * contiguous caches or paged ones with power-of-two blocks of at least 16 tokens; otherwise
+ * POD_ERR_UNSUPPORTED.  Not chosen automatically: on this chip it ends a prefill-heavy batch
+ * 3-8 % sooner when launches are spaced out and ties with the fused kernel in a sustained loop,
+ * where the chip clocks down under the power the two kernels draw together.
+ * Also accepted with POD_MODE_PREFILL_ONLY and POD_MODE_DECODE_ONLY, which then run that
+ * configuration's prefill or decode kernel alone.  Like POD_MODE_STREAMS it creates streams and
+ * events on first use, is not meant for graph capture, and is rejected by pod_attn_forward_static. */
+#define POD_MODE_FLAG_PREFILL_HEAVY 0x400
+
 /* Which operation a workgroup takes first on its compute unit (Section 4.1, the two policies). */
 typedef enum {
     POD_POLICY_AUTO = 0,        /* proportional, but never more decode than prefill workgroups at the
@@ -214,12 +231,12 @@ pod_status pod_attn_plan_upload(const pod_attn_plan *plan, void *workspace, size
  * contiguous cache also needs kv_seq_stride to be a multiple of 8 elements), else POD_ERR_INVALID_ARG.
  * The device arrays are trusted: a seq_meta that differs from the planned one, or a block
  * table entry outside [0, n_blocks), is undefined behaviour.  `mode` is a pod_mode, optionally OR-ed with
- * POD_MODE_FLAG_NO_COMBINE.
+ * the POD_MODE_FLAG_ values above.
  * The call only launches kernels on `stream` (no allocation, no memset, no wait on the host), so
  * in the FUSED, SERIAL and single-operation modes it may be recorded into a HIP graph; the
- * STREAMS mode creates its two side streams and events on first use (they belong to the plan and are
- * destroyed with it; that first call must not run beside another call on the same plan from a second
- * host thread) and is not meant for capture.
+ * STREAMS mode (and the prefill-heavy configuration) creates two side streams per GPU, kept until the
+ * process ends, and three events per plan, destroyed with it, on first use (that first call must not
+ * run beside another call on the same plan from a second host thread) and is not meant for capture.
  * Two forward calls that use the same workspace must not overlap in time.
  */
 pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
@@ -244,7 +261,8 @@ pod_status pod_attn_forward(const void *prefill_q, const void *decode_q,
  * except:
  *   - a plan whose pod_attn_workspace_size exceeds POD_ATTN_STATIC_SCRATCH_BYTES is rejected with
  *     POD_ERR_WORKSPACE (the message gives both numbers) and nothing is launched;
- *   - POD_MODE_STREAMS is rejected with POD_ERR_UNSUPPORTED (it creates streams and events).
+ *   - POD_MODE_STREAMS, and POD_MODE_FUSED with POD_MODE_FLAG_PREFILL_HEAVY, are rejected with
+ *     POD_ERR_UNSUPPORTED (they create streams and events).
  * All calls on one GPU share that GPU's array: two calls of this entry point on the same GPU must
  * not overlap in time (not from two streams, not from two host threads); calls on different
  * GPUs are independent.  pod_attn_forward and its workspaces are not affected in any way.

@@ -117,6 +117,29 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     return a;
 }
 
+// The two streams the two-kernel modes run their kernels on: one pair per GPU, created at the
+// first such call on that GPU and kept until the process ends.  (A pair per plan would be spread
+// over the few hardware queues a process has in creation order, and a later plan's pair can land
+// on one queue, where its two kernels run one after the other.)
+pod_status side_streams(hipStream_t *s0, hipStream_t *s1)
+{
+    static std::mutex mu;
+    static hipStream_t pair[kMaxDevices][2] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "asking for the current device");
+    if (dev < 0 || dev >= kMaxDevices) return fail(POD_ERR_UNSUPPORTED, "device index beyond what the library tracks");
+    std::lock_guard<std::mutex> lock(mu);
+    for (hipStream_t &st : pair[dev])
+        if (!st) {
+            e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+            if (e != hipSuccess) { st = nullptr; return fail_hip(e, "creating side stream"); }
+        }
+    *s0 = pair[dev][0];
+    *s1 = pair[dev][1];
+    return POD_OK;
+}
+
 // Clear the counters at the head of `workspace` (with a kernel, not a memset) and copy the plan's
 // work tables behind them; returns when the copies have completed.
 pod_status upload_tables(const pod::Plan &p, void *workspace, hipStream_t s)
@@ -176,8 +199,6 @@ pod_status pod_attn_plan_create(const pod_attn_params *params, const int32_t *se
 void pod_attn_plan_destroy(pod_attn_plan *plan)
 {
     if (!plan) return;
-    for (void *&s : plan->p.side_stream)
-        if (s) { (void)hipStreamDestroy((hipStream_t)s); s = nullptr; }
     for (void *&e : plan->p.events)
         if (e) { (void)hipEventDestroy((hipEvent_t)e); e = nullptr; }
     delete plan;
@@ -278,7 +299,11 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
     const int n_req = p.prm.n_prefill + p.prm.n_decode;
     const bool no_combine = (mode & POD_MODE_FLAG_NO_COMBINE) != 0;
     const bool cta_parallel = (mode & POD_MODE_FLAG_CTA_PARALLEL) != 0;
-    mode &= ~(POD_MODE_FLAG_NO_COMBINE | POD_MODE_FLAG_CTA_PARALLEL);
+    const bool heavy = (mode & POD_MODE_FLAG_PREFILL_HEAVY) != 0;
+    mode &= ~(POD_MODE_FLAG_NO_COMBINE | POD_MODE_FLAG_CTA_PARALLEL | POD_MODE_FLAG_PREFILL_HEAVY);
+    if (heavy && cta_parallel) return fail(POD_ERR_INVALID_ARG, "POD_MODE_FLAG_PREFILL_HEAVY and POD_MODE_FLAG_CTA_PARALLEL exclude each other");
+    if (heavy && mode != POD_MODE_FUSED && mode != POD_MODE_DECODE_ONLY && mode != POD_MODE_PREFILL_ONLY)
+        return fail(POD_ERR_INVALID_ARG, "POD_MODE_FLAG_PREFILL_HEAVY goes with POD_MODE_FUSED (or with one operation alone)");
     if (cta_parallel && mode != POD_MODE_FUSED)
         return fail(POD_ERR_INVALID_ARG, "POD_MODE_FLAG_CTA_PARALLEL goes with POD_MODE_FUSED only");
     if (mode < POD_MODE_FUSED || mode > POD_MODE_DECODE_ONLY) return fail(POD_ERR_INVALID_ARG, "unknown mode");
@@ -287,8 +312,14 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
     if (p.prm.n_prefill > 0 && !prefill_q) return fail(POD_ERR_INVALID_ARG, "prefill_q is null");
     if (p.prm.n_decode > 0 && !decode_q) return fail(POD_ERR_INVALID_ARG, "decode_q is null");
     if (paged && !block_table) return fail(POD_ERR_INVALID_ARG, "block_table is null for a paged cache");
+    if (heavy) {
+        const bool block_wise = !paged || ((p.prm.block_size & (p.prm.block_size - 1)) == 0 && p.prm.block_size >= 16);
+        if (p.prm.head_dim != 128 || !block_wise)
+            return fail(POD_ERR_UNSUPPORTED, "the prefill-heavy configuration is built for head_dim 128 and contiguous or "
+                                             "power-of-two (>= 16) block caches");
+    }
     if (use_static) {
-        if (mode == POD_MODE_STREAMS)
+        if (mode == POD_MODE_STREAMS || (heavy && mode == POD_MODE_FUSED))
             return fail(POD_ERR_UNSUPPORTED, "the two-stream mode creates streams and events; it is not available "
                                              "from the entry point that allocates nothing");
         if (p.ws_bytes > pod::kStaticScratchBytes)
@@ -339,8 +370,49 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
     only_d.crows = a.crows + 2 * (size_t)p.n_crows_prefill;
     only_d.n_crows = a.n_crows - p.n_crows_prefill;
 
+    // Prefill kernel and decode kernel on the library's two side streams, forked from and joined
+    // back into the caller's stream; the merge follows on the caller's stream.
+    auto two_streams = [&](int prefill_kind, int decode_kind) -> pod_status {
+        hipStream_t s0 = nullptr, s1 = nullptr;
+        {
+            const pod_status ss = side_streams(&s0, &s1);
+            if (ss != POD_OK) return ss;
+        }
+        for (void *&ev : p.events)
+            if (!ev) {
+                hipEvent_t ne;
+                hipError_t ce = hipEventCreateWithFlags(&ne, hipEventDisableTiming);
+                if (ce != hipSuccess) return fail_hip(ce, "creating event");
+                ev = ne;
+            }
+        hipEvent_t fork = (hipEvent_t)p.events[0], j0 = (hipEvent_t)p.events[1], j1 = (hipEvent_t)p.events[2];
+        auto chk = [&](hipError_t x) { if (e == hipSuccess) e = x; };
+        chk(hipEventRecord(fork, s));
+        chk(hipStreamWaitEvent(s0, fork, 0));
+        chk(hipStreamWaitEvent(s1, fork, 0));
+        go(prefill_kind, a, s0);
+        go(decode_kind, a, s1);
+        chk(hipEventRecord(j0, s0));
+        chk(hipEventRecord(j1, s1));
+        chk(hipStreamWaitEvent(s, j0, 0));
+        chk(hipStreamWaitEvent(s, j1, 0));
+        go(pod::kLaunchCombine, a, s);
+        return POD_OK;
+    };
+
     switch (mode) {
     case POD_MODE_FUSED:
+        if (heavy) {
+            // two prefill workgroups and one light decode workgroup per compute unit, from two kernels
+            if (p.prm.n_prefill == 0 || p.prm.n_decode == 0) {
+                go(p.prm.n_decode == 0 ? pod::kLaunchPrefillHeavy : pod::kLaunchDecodeLite, a, s);
+                go(pod::kLaunchCombine, a, s);
+            } else {
+                const pod_status st = two_streams(pod::kLaunchPrefillHeavy, pod::kLaunchDecodeLite);
+                if (st != POD_OK) return st;
+            }
+            break;
+        }
         if (cta_parallel) {
             // one workgroup per work item: every decode workgroup is given its four units by index
             pod::KernelArgs c = a;
@@ -358,41 +430,16 @@ static pod_status forward_impl(const void *prefill_q, const void *decode_q, cons
         go(pod::kLaunchCombine, a, s);
         break;
     case POD_MODE_PREFILL_ONLY:
-        go(pod::kLaunchPrefill, a, s);
+        go(heavy ? pod::kLaunchPrefillHeavy : pod::kLaunchPrefill, a, s);
         go(pod::kLaunchCombine, only_p, s);
         break;
     case POD_MODE_DECODE_ONLY:
-        go(pod::kLaunchDecode, a, s);
+        go(heavy ? pod::kLaunchDecodeLite : pod::kLaunchDecode, a, s);
         go(pod::kLaunchCombine, only_d, s);
         break;
     case POD_MODE_STREAMS: {
-        for (void *&ss : p.side_stream)
-            if (!ss) {
-                hipStream_t ns;
-                hipError_t ce = hipStreamCreateWithFlags(&ns, hipStreamNonBlocking);
-                if (ce != hipSuccess) return fail_hip(ce, "creating side stream");
-                ss = ns;
-            }
-        for (void *&ev : p.events)
-            if (!ev) {
-                hipEvent_t ne;
-                hipError_t ce = hipEventCreateWithFlags(&ne, hipEventDisableTiming);
-                if (ce != hipSuccess) return fail_hip(ce, "creating event");
-                ev = ne;
-            }
-        hipStream_t s0 = (hipStream_t)p.side_stream[0], s1 = (hipStream_t)p.side_stream[1];
-        hipEvent_t fork = (hipEvent_t)p.events[0], j0 = (hipEvent_t)p.events[1], j1 = (hipEvent_t)p.events[2];
-        auto chk = [&](hipError_t x) { if (e == hipSuccess) e = x; };
-        chk(hipEventRecord(fork, s));
-        chk(hipStreamWaitEvent(s0, fork, 0));
-        chk(hipStreamWaitEvent(s1, fork, 0));
-        go(pod::kLaunchPrefill, a, s0);
-        go(pod::kLaunchDecode, a, s1);
-        chk(hipEventRecord(j0, s0));
-        chk(hipEventRecord(j1, s1));
-        chk(hipStreamWaitEvent(s, j0, 0));
-        chk(hipStreamWaitEvent(s, j1, 0));
-        go(pod::kLaunchCombine, a, s);
+        const pod_status st = two_streams(pod::kLaunchPrefill, pod::kLaunchDecode);
+        if (st != POD_OK) return st;
         break;
     }
     default:

@@ -315,9 +315,14 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
     // pass, which lie inside one block.
     const int wr_row = lane / CH, wr_pos = lane % CH;
     const int tok_bytes = token_elems * 2;
-    uint32_t k_src[NPASS], v_src[NPASS];
+    // Up to 128 channels the rows a lane loads in the passes of a tile are a multiple of 16 rows
+    // apart, which the swizzles do not see: one offset serves every pass, and the distance between
+    // the passes' rows (contiguous cache only) is added to the uniform base of the pass.
+    constexpr int NSRC = D <= 128 ? 1 : NPASS;
+    static_assert(D > 128 || (RPP % 16 == 0), "row(p) - row(0) must not reach the swizzles");
+    uint32_t k_src[NSRC], v_src[NSRC];
 #pragma unroll
-    for (int p = 0; p < NPASS; ++p) {
+    for (int p = 0; p < NSRC; ++p) {
         const int row = p * RPP + wave * RPW + wr_row;
         // contiguous: row inside the tile; paged: row inside the wavefront's rows of the pass, plus
         // the wavefront's fixed row inside its block in the 16-key-block case
@@ -327,6 +332,8 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         k_src[p] = (uint32_t)(src_row * tok_bytes + k_swizzle<D>(row, wr_pos) * 16);
         v_src[p] = (uint32_t)(src_row * tok_bytes + v_swizzle<D>(row, wr_pos) * 16);
     }
+    // bytes between the rows of consecutive passes, where the lane offsets above do not hold them
+    const int64_t pass_bytes = (NSRC == 1 && LAYOUT == kLayoutContiguous) ? (int64_t)RPP * tok_bytes : 0;
 
     const typename N::elem *kc = (const typename N::elem *)a.k_cache + it.kv_head * a.head_stride;
     const typename N::elem *vc = (const typename N::elem *)a.v_cache + it.kv_head * a.head_stride;
@@ -372,7 +379,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         if constexpr (LAYOUT == kLayoutContiguous) {
             const int64_t off = ((int64_t)cache_row * a.kv_seq_stride + (int64_t)j0 * token_elems) * 2;
 #pragma unroll
-            for (int p = 0; p < NPASS; ++p) tb.b[p] = off;
+            for (int p = 0; p < NPASS; ++p) tb.b[p] = off + p * pass_bytes;
         } else if constexpr (LAYOUT == kLayoutPaged16) {
             // the block size is a power of two in this layout; bytes per token need not be (the
             // K/V head count of a model or of its tensor-parallel shard can be 5, 6, 10, 40 ...)
@@ -397,7 +404,7 @@ __device__ __forceinline__ void prefill_item_run(const KernelArgs &a, const Pref
         for (int p = 0; p < NPASS; ++p) {
             const uint32_t dst = lds0 + (uint32_t)((is_k ? buf : 2 + buf) * L::kTileBytes +
                                                   (p * kWgThreads + wave * kWaveSize) * 16);
-            dma16(dst, is_k ? k_src[p] : v_src[p], src + tb.b[p]);
+            dma16(dst, is_k ? k_src[NSRC == 1 ? 0 : p] : v_src[NSRC == 1 ? 0 : p], src + tb.b[p]);
         }
     };
     auto tile_is_fast = [&](int jt) {
@@ -1211,6 +1218,294 @@ __global__ __launch_bounds__(kWgThreads, 2) void decode_kernel(KernelArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
+// The prefill-heavy configuration (the second of the two occupancy configurations of
+// Section 4.2.2).  A compute unit holds 512 registers per SIMD lane and 160 KB of LDS; a prefill
+// wavefront can be held to 208 registers and a prefill workgroup needs 64 KB, so two prefill
+// workgroups leave 96 registers per lane and 28 KB of LDS on every unit (measured: a third
+// workgroup with 28 KB is placed, one with 32 KB is not).  The decode workgroup below is built to
+// fit exactly there: launched beside the prefill kernel it runs as the third workgroup of every
+// unit, and the prefill work keeps both of its slots for the whole launch.  A register budget is a
+// property of a kernel, not of a workgroup, so the two operations are two kernels here, started
+// together on two streams; what places them on the same units is the resource arithmetic above
+// (the trace records of both kernels show where each workgroup ran).
+//
+// With so little room the decode wavefront cannot keep its K/V stream in registers: the V rows
+// of a 16-key step go straight into a 4 KB LDS region (direct-to-LDS loads, which need no
+// destination registers), the K rows are loaded in matrix-operand order (lane = key row, 16 bytes
+// of 8 channels) into 16 registers that are consumed by four matrix instructions as soon as they
+// arrive and re-requested at once for the next step.  One step is in flight per wavefront while
+// the previous one is computed: ~8 KB per wavefront, 32 KB per unit.  Alone on the chip that
+// streams within 3-10 % of the full decode worker; beside two prefill workgroups per unit at
+// about two thirds of it.
+// ------------------------------------------------------------------------------------------
+// Register budgets of the two kernels (the attribute below counts half of the unified file):
+// 2 x 208 + 96 = 512 per SIMD lane.
+constexpr int kHeavyPrefillVgprs = 208, kLiteVgprs = 96;
+static_assert(2 * kHeavyPrefillVgprs + kLiteVgprs <= 512, "two prefill wavefronts and one decode wavefront per SIMD");
+constexpr int kLiteLdsPerWave = 4 * 1024;      // V rows of one step: four groups of 4 keys x 256 bytes
+constexpr int kLiteLdsBytes = kWavesPerWg * kLiteLdsPerWave;
+
+template <int DT, int LAYOUT>
+__global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_num_vgpr(kLiteVgprs / 2))) void decode_lite_kernel(KernelArgs a)
+{
+    static_assert(LAYOUT == kLayoutContiguous || LAYOUT == kLayoutPaged16, "a step must lie in one block");
+    constexpr int D = 128, KS = D / 32, MB = D / 16, STEP = 16;
+    using N = Num<DT>;
+    using v8 = typename N::v8;
+    using elem = typename N::elem;
+    __shared__ __attribute__((aligned(4096))) unsigned char smem[kLiteLdsBytes];
+    __shared__ int flag;
+    const uint64_t t_start = a.trace ? wall_clock64() : 0;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int n16 = lane & 15;                     // K: key row of this lane; Q, S, P, O: query column (head of the group)
+    const int b4 = lane >> 4;                      // K, Q: 8-channel piece of a 32-channel slice; S, P: keys 4*b4 .. 4*b4+3
+    const int group = a.group;
+    const int tok_bytes = a.tok_stride * 2;
+    const bool col_ok = n16 < group;
+    const float c = a.scale_log2;
+    POD_LDS unsigned char *const lds_v = (POD_LDS unsigned char *)smem + wave * kLiteLdsPerWave;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds_v;
+    const POD_CONST int32_t *const dq = (const POD_CONST int32_t *)a.dq_begin;
+
+    // V in LDS.  Group g of a step (keys 4g .. 4g+3) is one direct load: lane (row b4, position
+    // n16) lands at byte 16 * lane of the group's 1 KB.  Which 16-byte chunk of its row a lane
+    // fetches is swizzled on the global side, chunk = position ^ (row << 2 | g), so that the
+    // transposing reads below (16 lanes: 4 rows x 32 bytes of one group, the four groups at once)
+    // spread over all banks.  Source offsets: row b4 of the group, the chunk for g = 0; group g
+    // flips bits 4-5 of it (rows are at least 256 bytes apart, so the row part is not touched).
+    const uint32_t v_src0 = (uint32_t)(b4 * tok_bytes + ((n16 ^ (b4 << 2)) << 4));
+    // Reader: key 4*b4 + r4 (group b4, row r4), channels mb*16 + (n16 & 3)*4 .. +3, i.e. chunk
+    // 2*mb + p1 and its upper or lower half; position = chunk ^ (r4 << 2 | b4).  Everything but mb
+    // is fixed per lane, and mb only flips bits 5-7.
+    const int r4 = n16 >> 2, p1 = (n16 >> 1) & 1;
+    const uint32_t v_rd0 = (uint32_t)(b4 * 1024 + r4 * 256 + ((p1 ^ ((r4 << 2) | b4)) << 4) + (n16 & 1) * 8);
+    // K in registers, in operand order: lane = (key row n16, channels 32*ks + 8*b4 .. +7).
+    const uint32_t k_src0 = (uint32_t)(n16 * tok_bytes + b4 * 16);
+
+    // ---- unit claims (the protocol of the decode worker: fixed first units, then the queues) ----
+    int cq = __builtin_amdgcn_readfirstlane((int)(__smid() >> 6)) & (kXcdQueues - 1), tried = 0;
+    auto claim_now = [&]() __attribute__((always_inline)) -> int {
+        uint32_t v = 0;
+        if (lane == 0) {
+            uint32_t *ctr = &a.hdr->next_dunit_xcd[cq][0];
+            asm volatile("global_atomic_add %0, %1, %2, off sc0\n\ts_waitcnt vmcnt(0)"
+                         : "=&v"(v) : "v"(ctr), "v"(1u) : "memory");
+        }
+        lane_test_done();
+        return (int)__builtin_amdgcn_readfirstlane(v);
+    };
+    auto claim_unit = [&]() __attribute__((always_inline)) -> int {
+        if (tried >= kXcdQueues) return -1;
+        int k = claim_now();
+        for (;;) {
+            const int q0 = dq[cq], q1 = dq[cq + 1];
+            if (k < q1 - q0) return q0 + k;
+            do {
+                cq = (cq + 1) & (kXcdQueues - 1);
+                ++tried;
+            } while (tried < kXcdQueues && dq[cq + 1] == dq[cq]);
+            if (tried >= kXcdQueues) return -1;
+            k = claim_now();
+        }
+    };
+
+    int n_done = 0;
+    const int seat = blockIdx.x;
+    int idx = seat < a.n_static_seats ? seat * kWavesPerWg + wave : claim_unit();
+    while (idx >= 0 && idx < a.n_dunits) {
+        idx = __builtin_amdgcn_readfirstlane(idx);
+        const uint64_t tb = a.evlog ? wall_clock64() : 0;
+        const POD_CONST int32_t *w = (const POD_CONST int32_t *)a.dunits + 8 * (int64_t)idx;
+        const int kv_head = w[1], t0 = w[2], t1 = w[3], prow0 = w[4], q_start = w[6], cache_row = w[7];
+        const elem *kc = (const elem *)a.k_cache + kv_head * a.head_stride;
+        const elem *vc = (const elem *)a.v_cache + kv_head * a.head_stride;
+        const POD_CONST int32_t *table = (const POD_CONST int32_t *)a.block_table +
+                                         (int64_t)cache_row * a.max_blocks_per_seq;
+        // element offset (head 0, channel 0) of key t, a multiple of 16: a step lies in one block
+        auto base_of = [&](int t) __attribute__((always_inline)) -> int64_t {
+            if constexpr (LAYOUT == kLayoutContiguous) {
+                return (int64_t)cache_row * a.kv_seq_stride + (int64_t)t * a.tok_stride;
+            } else {
+                const int blk = table[t >> a.bs_shift];
+                return (int64_t)blk * a.block_elems + (int64_t)(t & (a.block_size - 1)) * a.tok_stride;
+            }
+        };
+        // query heads of the group: columns of the products, zero beyond the group
+        v8 q[KS];
+        {
+            const char *qb = (const char *)((const elem *)a.decode_q +
+                                            ((int64_t)q_start * a.n_q_heads + kv_head * group) * D);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = {0u, 0u, 0u, 0u};
+                if (col_ok) raw = load16(qb + (n16 * D + ks * 32 + b4 * 8) * 2);
+                q[ks] = __builtin_bit_cast(v8, raw);
+            }
+        }
+        f32x4 o[MB];
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m_run = neg_inf(), l_run = 0.f;
+
+        // Requests.  Keys past the unit's end re-read its last key (finite data; masked out of the
+        // softmax by index), so every address is inside the unit's rows.
+        u32x4 kreg[KS];
+        // The lane offsets of a ragged last step are worked out where they are needed, from copies
+        // the compiler cannot see through: otherwise it computes them ahead of the loop and holds a
+        // dozen registers for a path taken once per unit.
+        auto request_k = [&](int t) __attribute__((always_inline)) {
+            const char *kb = (const char *)(kc + base_of(t));
+            const int n_valid = min(t1 - t, STEP);
+            uint32_t off = k_src0;
+            if (n_valid < STEP) {
+                uint32_t row = (uint32_t)n16, piece = (uint32_t)b4;
+                asm volatile("" : "+v"(row), "+v"(piece));
+                off = min(row, (uint32_t)(n_valid - 1)) * (uint32_t)tok_bytes + piece * 16u;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kreg[ks] = load16_stream(kb + off + ks * 64);
+        };
+        auto request_v = [&](int t) __attribute__((always_inline)) {
+            const char *vb = (const char *)(vc + base_of(t));
+            const int n_valid = min(t1 - t, STEP);
+            if (n_valid == STEP) {
+                uint32_t src = v_src0;
+                asm volatile("" : "+v"(src));
+#pragma unroll
+                for (int g = 0; g < 4; ++g) dma16(lds0 + g * 1024, src ^ (uint32_t)(g << 4), vb + (int64_t)4 * g * tok_bytes);
+            } else {
+                uint32_t row = (uint32_t)b4, pos = (uint32_t)n16;
+                asm volatile("" : "+v"(row), "+v"(pos));
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint32_t src_row = min(4u * g + row, (uint32_t)(n_valid - 1));
+                    dma16(lds0 + g * 1024, src_row * (uint32_t)tok_bytes + ((pos ^ ((row << 2) | g)) << 4), vb);
+                }
+            }
+        };
+
+        request_k(t0);
+        request_v(t0);
+        for (int t = t0; t < t1; t += STEP) {
+            const bool more = t + STEP < t1;
+            // S^T = K Q^T: register r holds key t + 4*b4 + r of query column n16
+            f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) s = N::mfma16(__builtin_bit_cast(v8, kreg[ks]), q[ks], s);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) request_k(t + STEP);                    // into the registers just consumed
+            const int n_valid = min(t1 - t, STEP) - 4 * b4;   // keys of this lane that exist
+#pragma unroll
+            for (int r = 0; r < 4; ++r) s[r] = (r < n_valid) ? s[r] : neg_inf();
+            float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+            mx = max_across_32(max_across_16(mx)) * c;
+            const bool grow = mx > m_run + kMaxSlack;         // also true for the first key
+            if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                const float alpha = grow ? fast_exp2(m_run - mx) : 1.f;
+                m_run = grow ? mx : m_run;
+                l_run *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) o[mb] = o[mb] * alpha;
+            }
+            const float m_use = (m_run == neg_inf()) ? 0.f : m_run;
+            typename N::v4 pk;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = fast_exp2(__builtin_fmaf(s[r], c, -m_use));
+                l_run += p;
+                pk[r] = (elem)p;
+            }
+            // The V rows of this step were requested one step ago; the only requests younger than
+            // them are the four K loads just issued.
+            if (more) wait_loads_but<KS>();
+            else wait_all_loads();
+            // O^T += V^T P^T: rows = channels, contraction over the 16 keys in S's register order.
+            // The address of block mb is one XOR away from the lane's base (kept opaque so that the
+            // eight addresses are not held in registers); reads run two blocks ahead of their use.
+            {
+                uint32_t v_base = lds0 + v_rd0;           // the region is 4 KB aligned: bits 5-7 are the lane's own
+                asm volatile("" : "+v"(v_base));
+                constexpr int kAheadV = 2;
+                auto v_at = [&](int mb) __attribute__((always_inline)) {
+                    return lds_read_tr((const POD_LDS unsigned char *)(uintptr_t)(v_base ^ (uint32_t)(mb << 5)));
+                };
+                s16x4 vv[MB];
+#pragma unroll
+                for (int mb = 0; mb < kAheadV; ++mb) vv[mb] = v_at(mb);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    if (mb + kAheadV < MB) vv[mb + kAheadV] = v_at(mb + kAheadV);
+                    o[mb] = N::mfma16k16(vv[mb], pk, o[mb]);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, kAheadV, 0);
+#pragma unroll
+                for (int mb = 0; mb < MB - kAheadV; ++mb) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, kAheadV, 0);
+            }
+            // the region is free once the reads have returned
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (more) request_v(t + STEP);
+        }
+
+        // o[mb][r] is channel mb*16 + 4*b4 + r of query column n16
+        const float l_tot = sum_across_32(sum_across_16(l_run));
+        if (col_ok) {
+            if (prow0 < 0) {
+                const float inv = 1.f / l_tot;
+                elem *op = (elem *)a.out +
+                    ((int64_t)(a.n_prefill_rows + q_start) * a.n_q_heads + kv_head * group + n16) * D;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    typename N::v4 wv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) wv[e] = (elem)(o[mb][e] * inv);
+                    *(typename N::v4 *)(op + mb * 16 + 4 * b4) = wv;
+                }
+            } else {
+                const int64_t prow = (int64_t)prow0 + n16;
+                float *po = a.part_o + prow * D;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) *(f32x4 *)(po + mb * 16 + 4 * b4) = o[mb];
+                if (b4 == 0) {
+                    a.part_ml[prow * 2 + 0] = m_run;
+                    a.part_ml[prow * 2 + 1] = l_tot;
+                }
+            }
+        }
+        lane_test_done();
+        if (a.evlog) {
+            if (lane == 0) log_event(a, kDecode, idx, tb);
+            lane_test_done();
+        }
+        ++n_done;
+        idx = claim_unit();
+    }
+    if (a.trace) {
+        __syncthreads();
+        if (threadIdx.x == 0)
+            write_trace(a, a.n_pitems + blockIdx.x, __smid() & (kCuSlots - 1), kDecode, n_done, 0, t_start, wall_clock64());
+    }
+    finish_and_reset(a.hdr, &flag);
+}
+
+// The prefill kernel of that configuration: the stand-alone prefill kernel, held to 208 registers
+// (seven values go to scratch memory at head_dim 128; the kernel measures 1-3 % faster, not
+// slower) so that two of its workgroups and one light decode workgroup fill a unit's register file.
+template <int DT, int D, int LAYOUT>
+__global__ __launch_bounds__(kWgThreads, 2) __attribute__((amdgpu_num_vgpr(kHeavyPrefillVgprs / 2))) void prefill_heavy_kernel(KernelArgs a)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[PrefillLds<D>::kBytes];
+    const uint64_t t0 = a.trace ? wall_clock64() : 0;
+    prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
+    if (a.trace && threadIdx.x == 0)
+        write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
+}
+
+// ------------------------------------------------------------------------------------------
 // Fused kernel.  One resident round of workgroups (two per compute unit); each binds its first
 // operation after it has been placed on a compute unit (Section 4.1): the leader reads the
 // hardware unit id, takes a ticket from that unit's counter and chooses the operation that keeps
@@ -1415,6 +1710,22 @@ static hipError_t launch_variant(int which, const KernelArgs &a, hipStream_t str
     case kLaunchFusedCta:
         if (a.n_pitems + a.n_dctas > 0)
             fused_cta_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems + a.n_dctas), dim3(kWgThreads), 0, stream>>>(a);
+        break;
+    case kLaunchPrefillHeavy:
+        if constexpr (D == 128 && LAYOUT != kLayoutPagedAny) {
+            if (a.n_pitems > 0)
+                prefill_heavy_kernel<DT, D, LAYOUT><<<dim3(a.n_pitems), dim3(kWgThreads), 0, stream>>>(a);
+        } else {
+            return hipErrorInvalidValue;
+        }
+        break;
+    case kLaunchDecodeLite:
+        if constexpr (D == 128 && LAYOUT != kLayoutPagedAny) {
+            if (a.n_dwgs > 0)
+                decode_lite_kernel<DT, LAYOUT><<<dim3(a.n_dwgs), dim3(kWgThreads), 0, stream>>>(a);
+        } else {
+            return hipErrorInvalidValue;
+        }
         break;
     case kLaunchCombine:
         if (a.n_crows > 0) {

@@ -6,7 +6,8 @@
 
 namespace pod {
 
-enum LaunchKind : int { kLaunchPrefill = 0, kLaunchDecode = 1, kLaunchFused = 2, kLaunchCombine = 3, kLaunchFusedCta = 4 };
+enum LaunchKind : int { kLaunchPrefill = 0, kLaunchDecode = 1, kLaunchFused = 2, kLaunchCombine = 3, kLaunchFusedCta = 4,
+                        kLaunchPrefillHeavy = 5, kLaunchDecodeLite = 6 };
 
 // Enqueue one kernel of the given kind for (dtype, head_dim, layout) on `stream`.
 hipError_t launch(int which, const KernelArgs &a, int dtype, int head_dim, bool paged, hipStream_t stream);

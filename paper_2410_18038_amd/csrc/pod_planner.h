@@ -35,8 +35,7 @@ struct Plan {
     // byte offsets inside the workspace (each 256-byte aligned)
     size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_dq = 0, off_part_o = 0, off_part_ml = 0;
     size_t ws_bytes = 0;
-    // side streams and events of the two-stream mode, created on first use
-    void *side_stream[2] = {nullptr, nullptr};
+    // events of the two-kernel modes (fork, two joins), created on first use
     void *events[3] = {nullptr, nullptr, nullptr};
     void *trace = nullptr;                  // device buffer for TraceRecords, or null
     size_t trace_bytes = 0;

@@ -20,9 +20,13 @@ F16, BF16 = 0, 1
 MODE_FUSED, MODE_SERIAL, MODE_STREAMS, MODE_PREFILL_ONLY, MODE_DECODE_ONLY = range(5)
 MODE_FLAG_NO_COMBINE = 0x100
 MODE_FLAG_CTA_PARALLEL = 0x200
+MODE_FLAG_PREFILL_HEAVY = 0x400
 MODES = {"fused": MODE_FUSED, "serial": MODE_SERIAL, "streams": MODE_STREAMS,
          "prefill_only": MODE_PREFILL_ONLY, "decode_only": MODE_DECODE_ONLY,
-         "fused_cta": MODE_FUSED | MODE_FLAG_CTA_PARALLEL}
+         "fused_cta": MODE_FUSED | MODE_FLAG_CTA_PARALLEL,
+         "fused_heavy": MODE_FUSED | MODE_FLAG_PREFILL_HEAVY,
+         "prefill_only_heavy": MODE_PREFILL_ONLY | MODE_FLAG_PREFILL_HEAVY,
+         "decode_only_lite": MODE_DECODE_ONLY | MODE_FLAG_PREFILL_HEAVY}
 POLICY_AUTO, POLICY_ALTERNATE, POLICY_PROPORTIONAL = 0, 1, 2
 KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 

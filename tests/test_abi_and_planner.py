@@ -166,6 +166,39 @@ def test_static_scratch_entry_point_checks_sizes_before_touching_the_gpu():
     plan.close()
 
 
+def test_prefill_heavy_flag_is_checked_before_touching_the_gpu():
+    """The prefill-heavy configuration goes with the fused mode (or one operation alone), not with
+    the CTA-parallel launch, and only with the shapes its kernels are built for; the entry point
+    that allocates nothing refuses it, as it refuses the two-stream mode (runs without a GPU)."""
+    heavy = pod.MODE_FLAG_PREFILL_HEAVY
+    b = wl.config_batch(1)                                       # head_dim 64: not built
+    plan = pod.pod_attn_plan_create(params_for(b), b.seq_meta)
+    ws = pod.pod_attn_workspace_size(plan)
+    args = (256, 256, 256, 256, 256, 0, 256, plan, 256, ws)
+    for mode, status in [(pod.MODE_FUSED | heavy | pod.MODE_FLAG_CTA_PARALLEL, -1), (pod.MODE_SERIAL | heavy, -1),
+                         (pod.MODE_STREAMS | heavy, -1), (pod.MODE_FUSED | heavy, -2), (pod.MODE_DECODE_ONLY | heavy, -2)]:
+        with pytest.raises(pod.PodError) as e:
+            pod.pod_attn_forward(*args, mode)
+        assert e.value.status == status, (mode, str(e.value))
+    plan.close()
+    meta = np.array([[0, 64, 64, 0], [0, 1, 100, 1]], dtype=np.int32)
+    for block_size, ok in [(0, True), (16, True), (64, True), (8, False), (48, False)]:
+        prm = pod.make_params(n_prefill=1, n_decode=1, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.F16,
+                              softmax_scale=128 ** -0.5, block_size=block_size, max_blocks_per_seq=16 if block_size else 0,
+                              n_cache_rows=2, n_blocks=64 if block_size else 0, kv_seq_stride=0 if block_size else 128 * 2 * 128,
+                              n_compute_units=256)
+        plan = pod.pod_attn_plan_create(prm, meta)
+        with pytest.raises(pod.PodError) as e:                   # the static entry point: refused whatever the shape
+            pod.pod_attn_forward_static(256, 256, 256, 256, 256, 256 if block_size else 0, 256, plan, mode=pod.MODE_FUSED | heavy)
+        assert e.value.status == -2
+        if not ok:
+            with pytest.raises(pod.PodError) as e:
+                pod.pod_attn_forward(256, 256, 256, 256, 256, 256, 256, plan, 256, pod.pod_attn_workspace_size(plan),
+                                     pod.MODE_FUSED | heavy)
+            assert e.value.status == -2 and "head_dim 128" in str(e.value)
+        plan.close()
+
+
 # -- planner: every (row, key) pair and every decode token is covered exactly once --------------- #
 def coverage_check(prm, meta):
     plan = pod.pod_attn_plan_create(prm, meta)

@@ -450,3 +450,97 @@ def test_both_operations_are_resident_on_every_compute_unit(config):
     assert n_items == info.n_prefill_items
     assert (trace["t_switch"] >= trace["t_begin"]).all() and (trace["t_end"] >= trace["t_switch"]).all()
     attn.close()
+
+
+# ---- the prefill-heavy configuration (Section 4.2.2's second configuration) --------------------------
+HEAVY_MODES = ["fused_heavy", "prefill_only_heavy", "decode_only_lite"]
+
+
+def check_rows_of(batch, mode):
+    """`check` for a mode that writes only one operation's rows."""
+    npr = batch.n_prefill_rows
+    rows = None
+    if mode.startswith("prefill_only"):
+        rows = np.arange(0, npr)
+    elif mode.startswith("decode_only"):
+        rows = np.arange(npr, batch.n_rows)
+    return check(batch, mode, rows=rows)
+
+
+@pytest.mark.parametrize("mode", HEAVY_MODES)
+@pytest.mark.parametrize("dtype", [wl.F16, wl.BF16])
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (16, 1), (10, 5)])
+@pytest.mark.parametrize("block_size", [0, 16, 64])
+def test_prefill_heavy_configuration_matches_the_oracle(mode, dtype, hq, hkv, block_size):
+    """Both kernels of the configuration, alone and together, over group sizes 1 to 16, a token size
+    that is no power of two, both cache layouts it is built for, and decode contexts that end
+    inside, at and just past a 16-key step."""
+    batch = wl.make_batch(
+        f"heavy-{hq}q{hkv}kv-bs{block_size}", prefill=[(70, 200), (129, 129)],
+        decode_kv_lens=[1, 15, 16, 17, 31, 33, 257, 700, 2049], n_q_heads=hq, n_kv_heads=hkv, head_dim=128,
+        dtype=dtype, seed=500 + hq + block_size, block_size=block_size, poison=float("nan"))
+    check_rows_of(batch, mode)
+
+
+def test_prefill_heavy_configuration_with_split_kv_and_head_major_cache():
+    batch = wl.make_batch("heavy-split", prefill=[(300, 2300)], decode_kv_lens=[5000, 77, 1234, 3000],
+                          n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.BF16, seed=41, block_size=16,
+                          poison=float("nan"))
+    for mode in HEAVY_MODES:
+        print(f"case {batch.name} mode={mode} forced splits", flush=True)
+        got, info = run_gpu(batch, mode, decode_chunk=256, prefill_split_len=512, max_prefill_waves=8)
+        assert info.max_decode_splits > 1 and info.max_prefill_splits > 1
+        want = oracle_out(batch)
+        npr = batch.n_prefill_rows
+        sl = slice(0, npr) if mode.startswith("prefill_only") else slice(npr, None) if mode.startswith("decode_only") else slice(None)
+        assert np.abs(got[sl] - want[sl]).max() <= TOL[batch.dtype]
+    hm = wl.to_head_major(wl.make_batch("heavy-hnd", prefill=[(40, 90)], decode_kv_lens=[3, 64, 999], n_q_heads=8,
+                                        n_kv_heads=2, head_dim=128, dtype=wl.F16, seed=42, block_size=32,
+                                        poison=float("nan")))
+    for mode in HEAVY_MODES:
+        check_rows_of(hm, mode)
+
+
+def test_prefill_heavy_configuration_is_refused_where_it_is_not_built():
+    batch = wl.make_batch("heavy-d64", prefill=[(40, 90)], decode_kv_lens=[3, 64], n_q_heads=4, n_kv_heads=2,
+                          head_dim=64, dtype=wl.F16, seed=43)
+    dev_batch = batch.to("cuda:0")
+    attn = pod.HybridAttention(dev_batch)
+    with pytest.raises(pod.PodError) as e:
+        attn.forward(dev_batch, mode=pod.MODES["fused_heavy"])
+    assert e.value.status == -2
+    attn.close()
+
+
+def test_prefill_heavy_configuration_places_three_workgroups_on_every_unit():
+    """What the configuration is for, read off the trace records of one launch of the MFMA-bound
+    benchmark batch: when a unit's decode workgroup starts, two prefill workgroups are running on
+    that unit, on at least 95 % of the units; every unit has one decode workgroup; the decode
+    kernel ends while the prefill kernel is still running; the output is within the parity bar."""
+    batch = wl.config_batch(4, device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    mode = pod.MODES["fused_heavy"]
+    for _ in range(3):
+        attn.forward(batch, mode=mode)
+    attn.enable_trace()
+    out = attn.forward(batch, mode=mode)
+    torch.cuda.synchronize()
+    info = attn.info
+    n_p, n_d = info.n_prefill_items, info.n_compute_units
+    trace = attn.trace.cpu().numpy().view(pod.TRACE_DTYPE)[: n_p + n_d].copy()
+    P, D = trace[:n_p], trace[n_p:]
+    assert (P["first_role"] == 0).all() and (D["first_role"] == 1).all() and (trace["t_end"] > 0).all()
+    units, per_unit = np.unique(D["cu"], return_counts=True)
+    assert len(units) >= 0.95 * info.n_compute_units and (per_unit == 1).mean() >= 0.95
+    settle = 500                                                  # 5 us of the 100 MHz clock
+    resident = np.array([int(((P["cu"] == d["cu"]) & (P["t_begin"] <= d["t_begin"] + settle) &
+                              (P["t_end"] > d["t_begin"] + settle)).sum()) for d in D])
+    print("prefill workgroups resident beside each decode workgroup:", np.bincount(resident).tolist(), flush=True)
+    assert (resident == 2).mean() >= 0.95
+    assert int(D["n_first"].sum()) > 0                           # units run by the first wavefront of each workgroup
+    assert D["t_end"].max() < P["t_end"].max()
+    rows = np.concatenate([np.arange(0, batch.n_prefill_rows, 97), np.arange(batch.n_prefill_rows, batch.n_rows)])
+    want = oracle_out(batch, rows=rows)
+    got = out.to(torch.float64).cpu().numpy()[rows]
+    assert np.abs(got - want).max() <= TOL[batch.dtype]
+    attn.close()
