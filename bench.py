@@ -164,8 +164,9 @@ def wall_us_per_step(fn, steps, warmup, torch):
     return (time.perf_counter() - t1) / steps * 1e6
 
 
-KERNEL_OF_MODE = { "serial": "prefill_kernel + decode_kernel",
-                  "streams": "prefill_kernel + decode_kernel"}
+KERNEL_OF_MODE = {"serial": "prefill_kernel + decode_kernel",
+                  "streams": "prefill_kernel + decode_kernel",
+                  "fused_heavy": "prefill_heavy_kernel + decode_lite_kernel"}
 
 
 def oracle_check(batch, out, wl, torch):
@@ -208,8 +209,13 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     baseline_modes = (pod.MODE_SERIAL, pod.MODE_STREAMS, pod.MODE_PREFILL_ONLY)
 
     def fwd(mode):
-        which = attn_base if (mode & 0xff) in baseline_modes else attn
+        # the prefill-heavy configuration also runs a stand-alone prefill kernel with both slots
+        stand_alone = (mode & 0xff) in baseline_modes or (mode & pod.MODE_FLAG_PREFILL_HEAVY)
+        which = attn_base if stand_alone else attn
         return lambda: which.forward(batch, out=out, mode=mode)
+
+    bs = batch.block_size
+    heavy_built = batch.head_dim == 128 and (bs == 0 or (bs >= 16 and bs & (bs - 1) == 0))
 
     flops = batch.prefill_flops()
     kv_bytes = batch.kv_bytes()
@@ -249,7 +255,9 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
     # --- timing: every mode the same way (exactly `steps` calls bracketed by synchronisation), ----
     # --- plus per-call HIP-event times on the launch stream for the spread ------------------------
     results = {}
-    for name in ("fused", "serial", "streams", "prefill_only", "decode_only", "fused_cta"):
+    for name in ("fused", "serial", "streams", "prefill_only", "decode_only", "fused_cta", "fused_heavy"):
+        if name == "fused_heavy" and not heavy_built:
+            continue
         f = fwd(pod.MODES[name])
         wall = wall_us_per_step(f, steps, warmup, torch)
         ev = event_times_us(f, steps, torch)
@@ -261,6 +269,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         "workload": batch.name, "config": config, "batch_index": batch_index,
         "fused_us": results["fused"]["wall_us"], "serial_us": results["serial"]["wall_us"],
         "streams_us": results["streams"]["wall_us"], "fused_cta_parallel_us": results["fused_cta"]["wall_us"],
+        "prefill_heavy_us": results["fused_heavy"]["wall_us"] if heavy_built else None,
         "overlap_roofline_us": t_roof_us, "bound": bound,
         "pct_of_overlap_roofline": 100.0 * t_roof_us / value_us,
         "frac": t_roof_us / value_us,
@@ -441,7 +450,8 @@ def main():
     ap.add_argument("--no-configs", action="store_true",
                     help="time the headline batch only (no `configs` array with the other benchmark batches)")
     ap.add_argument("--batch-index", type=int, default=0, help="batch of the config-5 ratio sweep (0..11)")
-    ap.add_argument("--mode", default="fused", choices=["fused", "serial", "streams"])
+    ap.add_argument("--mode", default="fused", choices=["fused", "serial", "streams", "fused_heavy"],
+                    help="which schedule the headline value times (fused_heavy: the prefill-heavy configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the HBM-read and MFMA peak probes")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -548,14 +558,16 @@ def main():
                          fused_us=rec["modes"]["fused"]["wall_us"], serial_us=rec["modes"]["serial"]["wall_us"],
                          streams_us=rec["modes"]["streams"]["wall_us"],
                          fused_cta_parallel_us=rec["modes"]["fused_cta"]["wall_us"],
+                         prefill_heavy_us=rec["modes"].get("fused_heavy", {}).get("wall_us"),
                          frac=rec["pct_of_overlap_roofline"] / 100.0,
                          bound=rec["roofline"]["bound"], headline=True)
             else:
                 torch.cuda.empty_cache()
                 r = run_config(c, i, args.steps, args.warmup, False, "fused", torch, pod, wl, None, headline=False)
                 r.pop("modes")
+            heavy_txt = f"prefill-heavy {r['prefill_heavy_us']:.1f} us, " if r.get("prefill_heavy_us") else ""
             log(f"[bench] {r['workload']}: fused {r['fused_us']:.1f} us, serial {r['serial_us']:.1f} us, "
-                f"streams {r['streams_us']:.1f} us, {r['pct_of_overlap_roofline']:.1f}% of overlap roofline, "
+                f"streams {r['streams_us']:.1f} us, {heavy_txt}{r['pct_of_overlap_roofline']:.1f}% of overlap roofline, "
                 f"x{r['speedup_vs_serial']:.3f} vs serial, max-abs err {r['max_abs_err_vs_oracle']:.1e}")
             others.append(r)
         rec["configs"] = others
