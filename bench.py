@@ -35,15 +35,15 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): {kernel: FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per launch}  (files under profiles/)
-    (2, 0): {"fused_kernel": 4407163290, "fused_cta_kernel": 4609443840},
-    #   fused_kernel: 2141097.2 KiB fetched, 21676.0 KiB written
-    #   fused_cta_kernel: 2239540.2 KiB fetched, 22329.6 KiB written
-    (3, 0): {"fused_kernel": 4993989018, "fused_cta_kernel": 5158550426},
-    #   fused_kernel: 2417917.5 KiB fetched, 41107.4 KiB written
-    #   fused_cta_kernel: 2498350.1 KiB fetched, 40946.7 KiB written
-    (4, 0): {"fused_kernel": 2610979840, "fused_cta_kernel": 2764604314},
-    #   fused_kernel: 1254961.4 KiB fetched, 39862.2 KiB written
-    #   fused_cta_kernel: 1329632.5 KiB fetched, 40543.9 KiB written
+    (2, 0): {"fused_kernel": 4417563750, "fused_cta_kernel": 4637273498},
+    #   fused_kernel: 2146195.7 KiB fetched, 21635.7 KiB written
+    #   fused_cta_kernel: 2253190.4 KiB fetched, 22206.6 KiB written
+    (3, 0): {"fused_kernel": 4993689805, "fused_cta_kernel": 5150964326},
+    #   fused_kernel: 2417771.2 KiB fetched, 41107.8 KiB written
+    #   fused_cta_kernel: 2494646.4 KiB fetched, 40945.8 KiB written
+    (4, 0): {"fused_kernel": 2584120422, "fused_cta_kernel": 2764733440},
+    #   fused_kernel: 1241848.4 KiB fetched, 39858.3 KiB written
+    #   fused_cta_kernel: 1329794.6 KiB fetched, 40345.8 KiB written
 }
 
 
