@@ -69,8 +69,8 @@ typedef enum {
  * (one workgroup per prefill item or per four decode units; each takes its unit's ticket, picks
  * its operation, claims one work id, runs it and leaves), instead of as one resident round of
  * persistent workgroups (Section 4.4's variant, the default).  Same result bit for bit; exists so
- * that the two launch styles can be timed against each other (the persistent one is 3-17 % faster
- * on every benchmark batch of this chip once its clocks are up). */
+ * that the two launch styles can be timed against each other (once the chip's clocks are up the
+ * persistent one is level on the MFMA-bound benchmark batch and 6-17 % faster on all others). */
 #define POD_MODE_FLAG_CTA_PARALLEL 0x200
 
 /* May be OR-ed into POD_MODE_FUSED: the prefill-heavy occupancy configuration (Section 4.2.2 ships
