@@ -164,6 +164,67 @@ def wall_us_per_step(fn, steps, warmup, torch):
     return (time.perf_counter() - t1) / steps * 1e6
 
 
+def run_clock_by_mode(config, batch_index, torch, pod, wl):
+    """Graphics clock under each schedule in a sustained loop, and each schedule's time per launch
+    sustained, with a synchronisation after every launch, and with 20 ms of idle time before it."""
+    import re
+    import subprocess
+    import threading
+    batch = wl.config_batch(config, batch_index, device="cuda:0")
+    out = torch.empty((batch.n_rows, batch.n_q_heads, batch.head_dim), dtype=batch.torch_dtype, device="cuda:0")
+    attn = pod.HybridAttention(batch)
+    attn_base = pod.HybridAttention(batch, max_prefill_waves=2)
+    bs = batch.block_size
+    heavy_built = batch.head_dim == 128 and (bs == 0 or (bs >= 16 and bs & (bs - 1) == 0))
+    modes = ["decode_only", "prefill_only", "serial", "fused"] + (["fused_heavy"] if heavy_built else [])
+
+    def sample(stop, acc):
+        while not stop.is_set():
+            try:
+                r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=5)
+                m = re.search(r"sclk clock level: *\d+: *\((\d+)Mhz\)", r.stdout)
+                if m:
+                    acc.append(int(m.group(1)))
+            except (OSError, subprocess.SubprocessError):
+                pass
+            time.sleep(0.25)
+
+    print(f"graphics clock and time per launch by schedule: {batch.name} (one MI355X; sclk from rocm-smi while the "
+          f"schedule loops for 3 s; us per launch: in that loop / with a synchronisation after every launch / "
+          f"with 20 ms of idle time before every launch)")
+    for name in modes:
+        which = attn if name in ("fused", "decode_only") else attn_base
+        f = lambda: which.forward(batch, out=out, mode=pod.MODES[name])
+        stop, acc = threading.Event(), []
+        th = threading.Thread(target=sample, args=(stop, acc))
+        th.start()
+        t0 = time.perf_counter()
+        n = 0
+        while time.perf_counter() - t0 < 3.0:
+            for _ in range(50):
+                f()
+            torch.cuda.synchronize()
+            n += 50
+        sustained = (time.perf_counter() - t0) / n * 1e6
+        stop.set()
+        th.join()
+        one, spaced = [], []
+        for gap, dst in ((0.0, one), (0.02, spaced)):
+            for _ in range(12):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                time.sleep(gap)
+                e0.record()
+                f()
+                e1.record()
+                torch.cuda.synchronize()
+                dst.append(e0.elapsed_time(e1) * 1e3)
+        clk = f"{int(np.median(acc[2:] or acc or [0]))} MHz (min {min(acc or [0])}, max {max(acc or [0])}, {len(acc)} readings)"
+        print(f"  {name:14s} sclk {clk:48s} {sustained:7.0f} / {np.median(one):7.0f} / {np.median(spaced):7.0f} us")
+    attn.close()
+    attn_base.close()
+
+
 KERNEL_OF_MODE = {"serial": "prefill_kernel + decode_kernel",
                   "streams": "prefill_kernel + decode_kernel",
                   "fused_heavy": "prefill_heavy_kernel + decode_lite_kernel"}
@@ -472,6 +533,10 @@ def main():
     ap.add_argument("--trace-summary", action="store_true",
                     help="instead of timing, run one fused launch of --config with the library's workgroup trace "
                          "and event log switched on and print where and when the two operations ran (text)")
+    ap.add_argument("--clock-by-mode", action="store_true",
+                    help="instead of one timing, loop every schedule of --config for three seconds each while "
+                         "reading the graphics clock with rocm-smi, then time each schedule again with idle gaps "
+                         "between the launches (text): what the chip's clock management does to each schedule")
     ap.add_argument("--series-decodes", type=int, default=64)
     ap.add_argument("--series-out", default=None, help="write the chunk-series records to this file")
     args = ap.parse_args()
@@ -530,6 +595,9 @@ def main():
         print(trace_report.as_text(f"{batch.name} ({attn.info.n_prefill_items} prefill items, "
                                    f"{attn.info.n_decode_units} decode units, {attn.info.fused_grid} workgroups)", rep))
         attn.close()
+        return
+    if args.clock_by_mode:
+        run_clock_by_mode(args.config, args.batch_index, torch, pod, wl)
         return
     if args.chunk_series:
         rec = run_chunk_series(args.chunk_series, args.series_decodes, args.steps, args.warmup, torch, pod, wl)
