@@ -544,3 +544,37 @@ def test_prefill_heavy_configuration_places_three_workgroups_on_every_unit():
     got = out.to(torch.float64).cpu().numpy()[rows]
     assert np.abs(got - want).max() <= TOL[batch.dtype]
     attn.close()
+
+
+def test_prefill_heavy_configuration_with_many_short_units_and_long_contexts():
+    """The light decode kernel's own claim path: hundreds of units of 1..3 steps beside a few long
+    ones on a plan made for two compute units (every wavefront runs through many units, empties its
+    queue and tries the others), a plan with more decode workgroups than can be resident, and
+    contexts of 128K keys (sampled rows)."""
+    rng = np.random.Generator(np.random.PCG64(322))
+    lens = rng.integers(1, 41, size=150).tolist() + [5000, 17, 3001, 1, 16, 4097]
+    for hq, hkv, bs in [(8, 2, 16), (16, 1, 0)]:
+        batch = wl.make_batch(f"heavy-stream-{hq}/{hkv}-bs{bs}", prefill=[(70, 200)], decode_kv_lens=lens,
+                              n_q_heads=hq, n_kv_heads=hkv, head_dim=128, dtype=wl.F16, seed=4343 + bs,
+                              block_size=bs, poison=float("nan"))
+        for mode in ("fused_heavy", "decode_only_lite"):
+            print(f"case {batch.name} mode={mode}", flush=True)
+            got, info = run_gpu(batch, mode, n_compute_units=2, decode_chunk=512)
+            assert info.n_decode_units > 150 * hkv
+            want = oracle_out(batch)
+            sl = slice(batch.n_prefill_rows, None) if mode == "decode_only_lite" else slice(None)
+            assert np.abs(got[sl] - want[sl]).max() <= TOL[batch.dtype]
+    batch = wl.make_batch("heavy-oversubscribed", prefill=[(700, 1400)], decode_kv_lens=[300] * 900 + [2000] * 8,
+                          n_q_heads=8, n_kv_heads=4, head_dim=128, dtype=wl.BF16, seed=778, block_size=16)
+    check(batch, "fused_heavy", n_compute_units=1000, decode_chunk=128)
+    big = wl.make_batch("heavy-ctx128k", prefill=[(96, 131072)], decode_kv_lens=[131072, 100003, 65537],
+                        n_q_heads=8, n_kv_heads=2, head_dim=128, dtype=wl.BF16, block_size=16, seed=78, device="cuda:0")
+    attn = pod.HybridAttention(big)
+    out = attn.forward(big, mode=pod.MODES["fused_heavy"])
+    torch.cuda.synchronize()
+    rows = _sample_rows(big, 6, 3, seed=6)
+    want = oracle_out(big, rows=rows)
+    got = out[torch.from_numpy(rows.astype(np.int64)).to("cuda:0")].to(torch.float64).cpu().numpy()
+    assert bool(torch.isfinite(out.to(torch.float32)).all())
+    assert np.abs(got - want).max() <= TOL[big.dtype]
+    attn.close()
