@@ -567,8 +567,8 @@ def main():
         return
     if args.issue_probe:
         sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
-        print("instruction-mix probe: ns per matrix instruction, per wavefront and per SIMD (32x32x16 bf16; 32 cycles "
-              "at full rate)")
+        print("instruction-mix probe: ns per matrix instruction (last two lines: per vector instruction), per wavefront "
+              "and per SIMD (32x32x16 bf16; 32 cycles at full rate)")
         for variant, name in enumerate(pod.ISSUE_PROBE_VARIANTS):
             for w in (1, 2):
                 n = [0.0]

@@ -358,7 +358,10 @@ pod_status pod_attn_probe_mfma(int32_t iters, void *sink, double *flops_out, voi
  *      and the softmax work of one score in three stages one turn apart
  *   6  the same turn with two matrix instructions per LDS read and the work of two scores (a
  *      wavefront that holds two row blocks)
- * *matrix_ops_per_wave (host, may be NULL) receives the matrix instructions one wavefront issued;
+ *   7  no matrix instruction: eight independent multiply-adds per round
+ *   8  no matrix instruction: eight independent 2^x per round
+ * *matrix_ops_per_wave (host, may be NULL) receives the matrix instructions one wavefront issued
+ * (variants 7 and 8: the vector instructions);
  * the caller times the kernel.  `sink`: 4 writable bytes of device memory, never written in
  * practice.  Returns POD_ERR_INVALID_ARG for an unknown variant or bad arguments.
  */

@@ -246,6 +246,25 @@ __global__ __launch_bounds__(kThreads) void issue_turn_kernel(int iters, float s
     if (s == 12345.678f) sink[0] = s;
 }
 
+// Vector instructions alone: eight independent chains of one instruction kind.  What one wavefront
+// can issue by itself and what two reach together on a SIMD.
+template <int KIND>
+__global__ __launch_bounds__(kThreads) void issue_valu_kernel(int iters, float seed, float *sink)
+{
+    float x[8];
+    for (int i = 0; i < 8; ++i) x[i] = seed * 0.5f + 0.001f * (float)(threadIdx.x + i);
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (KIND == 0) asm volatile("v_fma_f32 %0, %0, %1, %1" : "+v"(x[i]) : "v"(seed));
+            else asm volatile("v_exp_f32 %0, %0" : "+v"(x[i]));
+        }
+    }
+    float s = 0.f;
+    for (int i = 0; i < 8; ++i) s += x[i];
+    if (s == 12345.678f) sink[0] = s;
+}
+
 }  // namespace
 
 extern "C" {
@@ -292,6 +311,8 @@ pod_status pod_attn_probe_issue(int32_t variant, int32_t iters, int32_t wgs_per_
     case 4: issue_mix_kernel<4, 0, 0, 0, 0, 1><<<grid, block, 0, s>>>(iters, 1.0f, out); break;
     case 5: issue_turn_kernel<1><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 3.0; break;
     case 6: issue_turn_kernel<2><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 6.0; break;
+    case 7: issue_valu_kernel<0><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 8.0; break;
+    case 8: issue_valu_kernel<1><<<grid, block, 0, s>>>(iters, 1.0f, out); per_iter = 8.0; break;
     default: return POD_ERR_INVALID_ARG;
     }
     if (matrix_ops_per_wave) *matrix_ops_per_wave = per_iter * (double)iters;

@@ -291,11 +291,14 @@ def pod_attn_probe_mfma(iters: int, sink: int, stream: int = 0) -> float:
 ISSUE_PROBE_VARIANTS = ["4 matrix instructions", "each + one 2^x", "each + the work of one softmax score (no dot product)",
                         "that + one 2-element dot product", "each + one 2-element dot product only",
                         "pipelined turn: LDS read, 1 matrix instruction, staged softmax of 1 score",
-                        "pipelined turn: LDS read, 2 matrix instructions, staged softmax of 2 scores"]
+                        "pipelined turn: LDS read, 2 matrix instructions, staged softmax of 2 scores",
+                        "no matrix instruction: 8 independent v_fma_f32 (ns per vector instruction)",
+                        "no matrix instruction: 8 independent v_exp_f32 (ns per vector instruction)"]
 
 
 def pod_attn_probe_issue(variant: int, iters: int, wgs_per_unit: int, sink: int, stream: int = 0) -> float:
-    """Enqueue one instruction-mix probe; returns the matrix instructions one wavefront issues."""
+    """Enqueue one instruction-mix probe; returns the matrix instructions (for the last two variants:
+    the vector instructions) one wavefront issues."""
     n = ctypes.c_double(0.0)
     status = lib().pod_attn_probe_issue(variant, iters, wgs_per_unit, ctypes.c_void_p(sink), ctypes.byref(n),
                                         ctypes.c_void_p(stream))
