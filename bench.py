@@ -35,15 +35,15 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): {kernel: FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per launch}  (files under profiles/)
-    (2, 0): {"fused_kernel": 4417563750, "fused_cta_kernel": 4637273498},
-    #   fused_kernel: 2146195.7 KiB fetched, 21635.7 KiB written
-    #   fused_cta_kernel: 2253190.4 KiB fetched, 22206.6 KiB written
-    (3, 0): {"fused_kernel": 4993689805, "fused_cta_kernel": 5150964326},
-    #   fused_kernel: 2417771.2 KiB fetched, 41107.8 KiB written
-    #   fused_cta_kernel: 2494646.4 KiB fetched, 40945.8 KiB written
-    (4, 0): {"fused_kernel": 2584120422, "fused_cta_kernel": 2764733440},
-    #   fused_kernel: 1241848.4 KiB fetched, 39858.3 KiB written
-    #   fused_cta_kernel: 1329794.6 KiB fetched, 40345.8 KiB written
+    (2, 0): {"fused_kernel": 4417379635, "fused_cta_kernel": 4625154560},
+    #   fused_kernel: 2146103.4 KiB fetched, 21640.5 KiB written
+    #   fused_cta_kernel: 2247262.2 KiB fetched, 22228.1 KiB written
+    (3, 0): {"fused_kernel": 4993820774, "fused_cta_kernel": 5155847680},
+    #   fused_kernel: 2417835.1 KiB fetched, 41107.9 KiB written
+    #   fused_cta_kernel: 2497030.6 KiB fetched, 40946.3 KiB written
+    (4, 0): {"fused_kernel": 2583423693, "fused_cta_kernel": 2759946445},
+    #   fused_kernel: 1241507.3 KiB fetched, 39860.1 KiB written
+    #   fused_cta_kernel: 1327490.5 KiB fetched, 40279.2 KiB written
 }
 
 

@@ -83,8 +83,8 @@ typedef enum {
  * rounding (the decode kernel adds its weights in another order).  Built for head_dim 128 and for
  * contiguous caches or paged ones with power-of-two blocks of at least 16 tokens; otherwise
  * POD_ERR_UNSUPPORTED.  Not chosen automatically: on this chip it ends a prefill-heavy batch
- * 3-8 % sooner when launches are spaced out and ties with the fused kernel in a sustained loop,
- * where the chip clocks down under the power the two kernels draw together.
+ * 3-8 % sooner when launches are spaced out and 0-2.5 % sooner in a sustained loop, where the chip
+ * clocks down under the power the two kernels draw together, and is slower on decode-bound batches.
  * Also accepted with POD_MODE_PREFILL_ONLY and POD_MODE_DECODE_ONLY, which then run that
  * configuration's prefill or decode kernel alone.  Like POD_MODE_STREAMS it creates streams and
  * events on first use, is not meant for graph capture, and is rejected by pod_attn_forward_static. */
@@ -318,6 +318,12 @@ int32_t pod_attn_simulate_launch(const pod_attn_plan *plan, const int32_t *unit_
  * Returns POD_ERR_INVALID_ARG when index is out of range.
  */
 pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
+/* The prefill item that workgroup `workgroup` of a stand-alone prefill kernel runs (SERIAL, STREAMS,
+ * PREFILL_ONLY and the prefill-heavy configuration launch one workgroup per item, and the
+ * hardware deals workgroups to the XCDs round-robin): the same items as above in another order,
+ * workgroup b taking the next item of queue b % 8, so that a K/V head's tiles are read through the
+ * L2 of the XCDs its queue belongs to. */
+pod_status pod_attn_plan_prefill_item_of_workgroup(const pod_attn_plan *plan, int32_t workgroup, int32_t out[8]);
 pod_status pod_attn_plan_decode_unit(const pod_attn_plan *plan, int32_t index, int32_t out[8]);
 
 /*

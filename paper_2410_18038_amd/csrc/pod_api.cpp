@@ -64,6 +64,7 @@ pod::KernelArgs make_args(const pod::Plan &p, const void *prefill_q, const void 
     a.seq_meta = seq_meta; a.block_table = block_table; a.out = out;
     a.hdr = (pod::WsHeader *)ws;
     a.pitems = (const pod::PrefillItem *)(ws + p.off_pitems);
+    a.pitems_by_wg = (const pod::PrefillItem *)(ws + p.off_pitems_by_wg);
     a.dunits = (const pod::DecodeUnit *)(ws + p.off_dunits);
     a.centries = (const pod::CombineEntry *)(ws + p.off_centries);
     a.crows = (const int32_t *)(ws + p.off_crows);
@@ -148,7 +149,8 @@ pod_status upload_tables(const pod::Plan &p, void *workspace, hipStream_t s)
     hipError_t e = pod::clear_header((pod::WsHeader *)ws, s);
     if (e != hipSuccess) return fail_hip(e, "clearing workspace counters");
     struct Part { size_t off; const void *src; size_t bytes; };
-    const Part parts[5] = {
+    const Part parts[6] = {
+        {p.off_pitems_by_wg, p.pitems_by_wg.data(), p.pitems_by_wg.size() * sizeof(pod::PrefillItem)},
         {p.off_dq, p.dq_begin, sizeof p.dq_begin},
         {p.off_pitems, p.pitems.data(), p.pitems.size() * sizeof(pod::PrefillItem)},
         {p.off_dunits, p.dunits.data(), p.dunits.size() * sizeof(pod::DecodeUnit)},
@@ -254,6 +256,16 @@ pod_status pod_attn_plan_prefill_item(const pod_attn_plan *plan, int32_t index, 
     if (!plan || !out || index < 0 || index >= (int32_t)plan->p.pitems.size())
         return fail(POD_ERR_INVALID_ARG, "prefill item index out of range");
     const pod::PrefillItem &it = plan->p.pitems[(size_t)index];
+    const int32_t v[8] = {it.req, it.kv_head, it.row0, it.n_rows, it.kv_begin, it.kv_end, it.prow0, it.split};
+    std::memcpy(out, v, sizeof v);
+    return POD_OK;
+}
+
+pod_status pod_attn_plan_prefill_item_of_workgroup(const pod_attn_plan *plan, int32_t workgroup, int32_t out[8])
+{
+    if (!plan || !out || workgroup < 0 || workgroup >= (int32_t)plan->p.pitems_by_wg.size())
+        return fail(POD_ERR_INVALID_ARG, "workgroup index out of range");
+    const pod::PrefillItem &it = plan->p.pitems_by_wg[(size_t)workgroup];
     const int32_t v[8] = {it.req, it.kv_head, it.row0, it.n_rows, it.kv_begin, it.kv_end, it.prow0, it.split};
     std::memcpy(out, v, sizeof v);
     return POD_OK;

@@ -128,6 +128,7 @@ struct KernelArgs {
     const int32_t *seq_meta, *block_table;
     void *out;
     const PrefillItem *pitems;
+    const PrefillItem *pitems_by_wg;       // the same items in workgroup order, for the kernels that run item blockIdx.x
     const DecodeUnit *dunits;
     const CombineEntry *centries;
     const int32_t *crows;                  // [n_crows][2] = (combine entry, row inside it): one merged output row each

@@ -1126,7 +1126,7 @@ __global__ __launch_bounds__(kWgThreads, 2) void prefill_kernel(KernelArgs a)
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[PrefillLds<D>::kBytes];
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
-    prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
+    prefill_item_run<DT, D, LAYOUT>(a, a.pitems_by_wg[blockIdx.x], smem);
     if (a.trace && threadIdx.x == 0)
         write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
 }
@@ -1500,7 +1500,7 @@ __global__ __launch_bounds__(kWgThreads, 2) __attribute__((amdgpu_num_vgpr(kHeav
 {
     __shared__ __attribute__((aligned(16))) unsigned char smem[PrefillLds<D>::kBytes];
     const uint64_t t0 = a.trace ? wall_clock64() : 0;
-    prefill_item_run<DT, D, LAYOUT>(a, a.pitems[blockIdx.x], smem);
+    prefill_item_run<DT, D, LAYOUT>(a, a.pitems_by_wg[blockIdx.x], smem);
     if (a.trace && threadIdx.x == 0)
         write_trace(a, blockIdx.x, __smid() & (kCuSlots - 1), kPrefill, 1, 0, t0, wall_clock64());
 }

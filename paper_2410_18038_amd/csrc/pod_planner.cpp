@@ -237,6 +237,26 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
             while (at < (int)plan.pitems.size() && queue_of(plan.pitems[(size_t)at]) < q) ++at;
             plan.pq_begin[q] = q == kXcdQueues ? (int)plan.pitems.size() : at;
         }
+        // Order for the kernels that take items by workgroup index (one workgroup per item, no
+        // claims): workgroup b runs on XCD b % 8 (measured: the dispatcher deals them round-robin
+        // without exception), so it gets the next item of queue b % 8 and a K/V head's tiles stay in
+        // the L2 of the XCDs its queue belongs to.  Queues of unequal length: what is left over goes
+        // to the workgroups whose own queue has run out.
+        {
+            const int n = (int)plan.pitems.size();
+            plan.pitems_by_wg.assign((size_t)n, PrefillItem{});
+            int next[kXcdQueues];
+            for (int q = 0; q < kXcdQueues; ++q) next[q] = plan.pq_begin[q];
+            std::vector<int> unfilled;
+            for (int b = 0; b < n; ++b) {
+                const int q = b % kXcdQueues;
+                if (next[q] < plan.pq_begin[q + 1]) plan.pitems_by_wg[(size_t)b] = plan.pitems[(size_t)next[q]++];
+                else unfilled.push_back(b);
+            }
+            size_t u = 0;
+            for (int q = 0; q < kXcdQueues; ++q)
+                while (next[q] < plan.pq_begin[q + 1]) plan.pitems_by_wg[(size_t)unfilled[u++]] = plan.pitems[(size_t)next[q]++];
+        }
     }
 
     // ---- decode units ------------------------------------------------------------------
@@ -358,6 +378,7 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     // ---- workspace layout --------------------------------------------------------------
     size_t off = align256(sizeof(WsHeader));
     plan.off_pitems = off;   off = align256(off + plan.pitems.size() * sizeof(PrefillItem));
+    plan.off_pitems_by_wg = off; off = align256(off + plan.pitems_by_wg.size() * sizeof(PrefillItem));
     plan.off_dunits = off;   off = align256(off + plan.dunits.size() * sizeof(DecodeUnit));
     plan.off_centries = off; off = align256(off + plan.centries.size() * sizeof(CombineEntry));
     plan.off_crows = off;    off = align256(off + plan.crows.size() * sizeof(int32_t));

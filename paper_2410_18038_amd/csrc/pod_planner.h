@@ -18,6 +18,9 @@ struct Plan {
     int group = 1;
     std::vector<int32_t> meta;              // host copy of seq_meta
     std::vector<PrefillItem> pitems;
+    // The same items in the order the stand-alone prefill kernels take them by workgroup index: the
+    // hardware deals workgroups to the XCDs round-robin, so workgroup b gets an item of queue b % 8.
+    std::vector<PrefillItem> pitems_by_wg;
     std::vector<DecodeUnit> dunits;
     std::vector<CombineEntry> centries;
     std::vector<int32_t> crows;             // (entry, row) pairs, prefill entries first
@@ -33,7 +36,7 @@ struct Plan {
     int n_dwgs = 0;                         // decode workers: workgroups of the stand-alone decode kernel, decode seats of the fused one
     int fused_grid = 0;                     // workgroups of the fused kernel
     // byte offsets inside the workspace (each 256-byte aligned)
-    size_t off_pitems = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_dq = 0, off_part_o = 0, off_part_ml = 0;
+    size_t off_pitems = 0, off_pitems_by_wg = 0, off_dunits = 0, off_centries = 0, off_crows = 0, off_dq = 0, off_part_o = 0, off_part_ml = 0;
     size_t ws_bytes = 0;
     // events of the two-kernel modes (fork, two joins), created on first use
     void *events[3] = {nullptr, nullptr, nullptr};

@@ -33,7 +33,7 @@ KV_TOKEN_MAJOR, KV_HEAD_MAJOR = 0, 1
 EXPORTS = ["pod_attn_plan_create", "pod_attn_plan_destroy", "pod_attn_plan_info_get",
            "pod_attn_workspace_size", "pod_attn_plan_set_trace", "pod_attn_plan_set_event_log",
            "pod_attn_plan_upload", "pod_attn_forward", "pod_attn_forward_static",
-           "pod_attn_role_for_ticket", "pod_attn_simulate_launch", "pod_attn_plan_prefill_item", "pod_attn_plan_decode_unit",
+           "pod_attn_role_for_ticket", "pod_attn_simulate_launch", "pod_attn_plan_prefill_item", "pod_attn_plan_prefill_item_of_workgroup", "pod_attn_plan_decode_unit",
            "pod_attn_plan_decode_queue",
            "pod_attn_probe_hbm_read", "pod_attn_probe_mfma", "pod_attn_probe_issue", "pod_attn_probe_colocation",
            "pod_attn_last_error", "pod_attn_version"]
@@ -111,6 +111,8 @@ def lib():
         L.pod_attn_simulate_launch.argtypes = [vp, i32p, ctypes.c_int32, i32p, ctypes.c_int32, i32p, i32p, i32p, i32p]
         L.pod_attn_plan_prefill_item.restype = ctypes.c_int
         L.pod_attn_plan_prefill_item.argtypes = [vp, ctypes.c_int32, i32p]
+        L.pod_attn_plan_prefill_item_of_workgroup.restype = ctypes.c_int
+        L.pod_attn_plan_prefill_item_of_workgroup.argtypes = [vp, ctypes.c_int32, i32p]
         L.pod_attn_plan_decode_unit.restype = ctypes.c_int
         L.pod_attn_plan_decode_unit.argtypes = [vp, ctypes.c_int32, i32p]
         L.pod_attn_plan_decode_queue.restype = ctypes.c_int
@@ -175,6 +177,10 @@ class Plan:
         n = self.info().n_prefill_items
         return np.array([pod_attn_plan_prefill_item(self, i) for i in range(n)], dtype=np.int32).reshape(n, 8)
 
+    def prefill_items_by_workgroup(self) -> np.ndarray:
+        n = self.info().n_prefill_items
+        return np.array([pod_attn_plan_prefill_item_of_workgroup(self, i) for i in range(n)], dtype=np.int32).reshape(n, 8)
+
     def decode_units(self) -> np.ndarray:
         n = self.info().n_decode_units
         return np.array([pod_attn_plan_decode_unit(self, i) for i in range(n)], dtype=np.int32).reshape(n, 8)
@@ -226,6 +232,12 @@ TRACE_DTYPE = np.dtype([("cu", np.int32), ("first_role", np.int32), ("n_first", 
 
 def pod_attn_workspace_size(plan: Plan) -> int:
     return int(lib().pod_attn_workspace_size(plan.handle))
+
+
+def pod_attn_plan_prefill_item_of_workgroup(plan: Plan, workgroup: int):
+    out = (ctypes.c_int32 * 8)()
+    _check(lib().pod_attn_plan_prefill_item_of_workgroup(plan.handle, workgroup, out))
+    return list(out)
 
 
 def pod_attn_plan_prefill_item(plan: Plan, index: int):

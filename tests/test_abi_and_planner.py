@@ -199,6 +199,27 @@ def test_prefill_heavy_flag_is_checked_before_touching_the_gpu():
         plan.close()
 
 
+def test_workgroup_order_of_prefill_items_keeps_a_kv_head_on_its_xcds():
+    """The stand-alone prefill kernels run item b of a second table in workgroup b, and the hardware
+    deals workgroups to the eight XCDs round-robin: the table must hold every item exactly once, and
+    the workgroups of one XCD (b % 8 equal) must work on as few K/V heads as the batch allows."""
+    cases = [(32, 4, 2048, 32768, 1), (32, 32, 1024, 4096, 4), (32, 8, 512, 8192, 1), (8, 2, 300, 1000, 2)]
+    for hq, hkv, q_len, kv_len, heads_per_xcd in cases:
+        meta = np.array([[0, q_len, kv_len, 0], [0, 1, 777, 1]], dtype=np.int32)
+        prm = pod.make_params(n_prefill=1, n_decode=1, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, dtype=wl.BF16,
+                              softmax_scale=128 ** -0.5, block_size=16, max_blocks_per_seq=kv_len // 16 + 1,
+                              n_cache_rows=2, n_blocks=2 * (kv_len // 16 + 1), n_compute_units=256, max_prefill_waves=2)
+        plan = pod.pod_attn_plan_create(prm, meta)
+        items, by_wg = plan.prefill_items(), plan.prefill_items_by_workgroup()
+        assert sorted(map(tuple, items.tolist())) == sorted(map(tuple, by_wg.tolist()))
+        for x in range(8):
+            heads = np.unique(by_wg[x::8, 1])
+            assert len(heads) <= heads_per_xcd, (hq, hkv, x, heads)
+        with pytest.raises(pod.PodError):
+            pod.pod_attn_plan_prefill_item_of_workgroup(plan, len(items))
+        plan.close()
+
+
 # -- planner: every (row, key) pair and every decode token is covered exactly once --------------- #
 def coverage_check(prm, meta):
     plan = pod.pod_attn_plan_create(prm, meta)
