@@ -331,6 +331,7 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
         "fused_us": results["fused"]["wall_us"], "serial_us": results["serial"]["wall_us"],
         "streams_us": results["streams"]["wall_us"], "fused_cta_parallel_us": results["fused_cta"]["wall_us"],
         "prefill_heavy_us": results["fused_heavy"]["wall_us"] if heavy_built else None,
+        "prefill_heavy_advised": bool(info.prefill_heavy_advised),   # the planner's reading of Section 4.2.2's choice
         "overlap_roofline_us": t_roof_us, "bound": bound,
         "pct_of_overlap_roofline": 100.0 * t_roof_us / value_us,
         "frac": t_roof_us / value_us,
@@ -371,7 +372,8 @@ def run_config(config, batch_index, steps, warmup, want_cpu, main_mode, torch, p
                    "decode_ctx_mean": float(batch.seq_meta[batch.n_prefill:, 2].mean()) if batch.n_decode else 0.0,
                    "kv_layout": f"paged{batch.block_size}" if batch.block_size else "contiguous",
                    "prefill_items": info.n_prefill_items, "decode_units": info.n_decode_units,
-                   "role_ratio": [info.prefill_ratio, info.decode_ratio]},
+                   "role_ratio": [info.prefill_ratio, info.decode_ratio],
+                   "prefill_heavy_advised": bool(info.prefill_heavy_advised)},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
                      "traffic": traffic,
                      "traffic_source": "rocprofv3 --pmc summaries under profiles/ (separate runs of this command), not this run",
@@ -627,6 +629,7 @@ def main():
                          streams_us=rec["modes"]["streams"]["wall_us"],
                          fused_cta_parallel_us=rec["modes"]["fused_cta"]["wall_us"],
                          prefill_heavy_us=rec["modes"].get("fused_heavy", {}).get("wall_us"),
+                         prefill_heavy_advised=rec["config"]["prefill_heavy_advised"],
                          frac=rec["pct_of_overlap_roofline"] / 100.0,
                          bound=rec["roofline"]["bound"], headline=True)
             else:

@@ -144,6 +144,11 @@ typedef struct {
     int64_t n_prefill_rows;     /* sum of q_len over prefill requests                            */
     int64_t n_partial_rows;     /* rows of fp32 partial output held in the workspace             */
     int64_t workspace_bytes;
+    int32_t prefill_heavy_advised; /* 1 when the batch is one the prefill-heavy configuration is built
+                                   for and its prefill work outweighs its decode stream (FLOP time
+                                   at the matrix peak above 1.2 x byte time at the HBM peak): the
+                                   caller may OR POD_MODE_FLAG_PREFILL_HEAVY into POD_MODE_FUSED  */
+    int32_t reserved0;
 } pod_attn_plan_info;
 
 typedef struct pod_attn_plan pod_attn_plan;   /* opaque, host memory, owned by the caller */

@@ -223,6 +223,8 @@ pod_status pod_attn_plan_info_get(const pod_attn_plan *plan, pod_attn_plan_info 
     info->n_prefill_rows = p.n_prefill_rows;
     info->n_partial_rows = p.n_partial_rows;
     info->workspace_bytes = (int64_t)p.ws_bytes;
+    info->prefill_heavy_advised = p.heavy_advised ? 1 : 0;
+    info->reserved0 = 0;
     return POD_OK;
 }
 

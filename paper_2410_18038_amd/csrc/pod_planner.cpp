@@ -375,6 +375,24 @@ pod_status build_plan(const pod_attn_params &prm, const int32_t *seq_meta, int n
     // that got a single workgroup would start it on prefill and be left without a decode worker).
     if (plan.n_dwgs == n_cus && !plan.pitems.empty()) plan.fused_grid = 2 * n_cus;
 
+    // ---- which occupancy configuration suits the batch (Section 4.2.2) ----------------------
+    // The prefill-heavy configuration pays when the prefill work outlasts the decode stream even
+    // though that stream is the slower one there: matrix time of the prefill (at the datasheet
+    // peak) above 1.2 x the time the batch's K/V bytes take at the HBM peak.
+    {
+        double pairs = 0.0, kv_tokens = 0.0;
+        for (int r = 0; r < n_req; ++r) {
+            const double q_len = seq_meta[4 * r + 1], kv_len = seq_meta[4 * r + 2];
+            kv_tokens += kv_len;
+            if (r < prm.n_prefill) pairs += q_len * (kv_len - q_len) + q_len * (q_len + 1.0) / 2.0;
+        }
+        const double flop_time = 4.0 * prm.head_dim * pairs * prm.n_q_heads / 2.5e15;
+        const double byte_time = kv_tokens * prm.n_kv_heads * prm.head_dim * 4.0 / 8.0e12;
+        const bool block_wise = prm.block_size == 0 || (prm.block_size >= 16 && (prm.block_size & (prm.block_size - 1)) == 0);
+        plan.heavy_advised = prm.head_dim == 128 && block_wise && prm.n_prefill > 0 && prm.n_decode > 0 &&
+                             flop_time > 1.2 * byte_time;
+    }
+
     // ---- workspace layout --------------------------------------------------------------
     size_t off = align256(sizeof(WsHeader));
     plan.off_pitems = off;   off = align256(off + plan.pitems.size() * sizeof(PrefillItem));

@@ -17,6 +17,7 @@ struct Plan {
     int n_cus = 256;
     int group = 1;
     std::vector<int32_t> meta;              // host copy of seq_meta
+    bool heavy_advised = false;             // see pod_attn_plan_info.prefill_heavy_advised
     std::vector<PrefillItem> pitems;
     // The same items in the order the stand-alone prefill kernels take them by workgroup index: the
     // hardware deals workgroups to the XCDs round-robin, so workgroup b gets an item of queue b % 8.

@@ -64,7 +64,8 @@ class PlanInfo(ctypes.Structure):
                 ("prefill_ratio", ctypes.c_int32), ("decode_ratio", ctypes.c_int32),
                 ("fused_grid", ctypes.c_int32), ("n_compute_units", ctypes.c_int32),
                 ("n_prefill_rows", ctypes.c_int64), ("n_partial_rows", ctypes.c_int64),
-                ("workspace_bytes", ctypes.c_int64)]
+                ("workspace_bytes", ctypes.c_int64), ("prefill_heavy_advised", ctypes.c_int32),
+                ("reserved0", ctypes.c_int32)]
 
 
 _lib = None

@@ -220,6 +220,35 @@ def test_workgroup_order_of_prefill_items_keeps_a_kv_head_on_its_xcds():
         plan.close()
 
 
+def test_planner_advises_the_prefill_heavy_configuration_where_prefill_outweighs_decode():
+    """Section 4.2.2 picks the occupancy configuration per batch.  Here the plan says which one suits
+    the batch (matrix time of the prefill above 1.2 x the byte time of the K/V stream, and a shape
+    the configuration is built for); of the benchmark batches that is the MFMA-bound one only."""
+    advised = {}
+    rng = np.random.Generator(np.random.PCG64(5))
+    shapes = {(2, 0): meta_only("c2", [(1024, 4096)], [4096] * 64, hq=32, hkv=32, block_size=0),
+              (3, 0): meta_only("c3", [(512, 8192)], rng.integers(2048, 16385, size=128).tolist()),
+              (4, 0): meta_only("c4", [(2048, 32768)], [32768] * 32, hq=32, hkv=4)}
+    for i, (chunk, nd) in enumerate(wl.RATIO_SWEEP):
+        shapes[(5, i)] = meta_only("c5", [(chunk, 4096)], rng.integers(4096, 16385, size=nd).tolist())
+    for key, (prm, meta) in shapes.items():
+        plan = pod.pod_attn_plan_create(prm, meta)
+        advised[key] = plan.info().prefill_heavy_advised
+        plan.close()
+    assert advised[(4, 0)] == 1
+    assert all(v == 0 for k, v in advised.items() if k != (4, 0))
+    # the same shape with 64 channels is not built, and a batch without decodes has nothing to co-run
+    meta = np.array([[0, 2048, 32768, 0], [0, 1, 4096, 1]], dtype=np.int32)
+    base = dict(n_prefill=1, n_decode=1, n_q_heads=32, n_kv_heads=4, head_dim=128, dtype=wl.BF16, softmax_scale=0.1,
+                block_size=16, max_blocks_per_seq=2049, n_cache_rows=2, n_blocks=4200, n_compute_units=256)
+    for change, want in [({}, 1), ({"head_dim": 64}, 0), ({"block_size": 48, "max_blocks_per_seq": 700}, 0),
+                         ({"n_decode": 0}, 0)]:
+        prm = pod.make_params(**{**base, **change})
+        plan = pod.pod_attn_plan_create(prm, meta[: prm.n_prefill + prm.n_decode])
+        assert plan.info().prefill_heavy_advised == want, change
+        plan.close()
+
+
 # -- planner: every (row, key) pair and every decode token is covered exactly once --------------- #
 def coverage_check(prm, meta):
     plan = pod.pod_attn_plan_create(prm, meta)
