@@ -225,6 +225,12 @@ __device__ __forceinline__ void dma16(uint32_t lds_addr, uint32_t voff, const vo
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
 }
+// Same, for data that is read once (the decode stream): marked non-temporal like load16_stream.
+__device__ __forceinline__ void dma16_stream(uint32_t lds_addr, uint32_t voff, const void *sbase)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+}
 __device__ __forceinline__ void dma16_vaddr(uint32_t lds_addr, const void *vaddr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
@@ -1373,14 +1379,14 @@ __global__ __launch_bounds__(kWgThreads) __attribute__((amdgpu_num_vgpr(kLiteVgp
                 uint32_t src = v_src0;
                 asm volatile("" : "+v"(src));
 #pragma unroll
-                for (int g = 0; g < 4; ++g) dma16(lds0 + g * 1024, src ^ (uint32_t)(g << 4), vb + (int64_t)4 * g * tok_bytes);
+                for (int g = 0; g < 4; ++g) dma16_stream(lds0 + g * 1024, src ^ (uint32_t)(g << 4), vb + (int64_t)4 * g * tok_bytes);
             } else {
                 uint32_t row = (uint32_t)b4, pos = (uint32_t)n16;
                 asm volatile("" : "+v"(row), "+v"(pos));
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const uint32_t src_row = min(4u * g + row, (uint32_t)(n_valid - 1));
-                    dma16(lds0 + g * 1024, src_row * (uint32_t)tok_bytes + ((pos ^ ((row << 2) | g)) << 4), vb);
+                    dma16_stream(lds0 + g * 1024, src_row * (uint32_t)tok_bytes + ((pos ^ ((row << 2) | g)) << 4), vb);
                 }
             }
         };
