@@ -35,15 +35,15 @@ PEAK_HBM = 8.0e12               # bytes/s, MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {
     # (config, batch_index): {kernel: FETCH_SIZE KiB x 2.0 (copy calibration: the counter reads half of a
     # plain copy's bytes) + WRITE_SIZE KiB x 1.0, per launch}  (files under profiles/)
-    (2, 0): {"fused_kernel": 4417379635, "fused_cta_kernel": 4625154560},
-    #   fused_kernel: 2146103.4 KiB fetched, 21640.5 KiB written
-    #   fused_cta_kernel: 2247262.2 KiB fetched, 22228.1 KiB written
-    (3, 0): {"fused_kernel": 4993820774, "fused_cta_kernel": 5155847680},
-    #   fused_kernel: 2417835.1 KiB fetched, 41107.9 KiB written
-    #   fused_cta_kernel: 2497030.6 KiB fetched, 40946.3 KiB written
-    (4, 0): {"fused_kernel": 2583423693, "fused_cta_kernel": 2759946445},
-    #   fused_kernel: 1241507.3 KiB fetched, 39860.1 KiB written
-    #   fused_cta_kernel: 1327490.5 KiB fetched, 40279.2 KiB written
+    (2, 0): {"fused_kernel": 4416896205, "fused_cta_kernel": 4623039283},
+    #   fused_kernel: 2145859.8 KiB fetched, 21655.6 KiB written
+    #   fused_cta_kernel: 2246222.3 KiB fetched, 22242.2 KiB written
+    (3, 0): {"fused_kernel": 4994009498, "fused_cta_kernel": 5153556582},
+    #   fused_kernel: 2417927.3 KiB fetched, 41107.8 KiB written
+    #   fused_cta_kernel: 2495912.2 KiB fetched, 40945.7 KiB written
+    (4, 0): {"fused_kernel": 2582235443, "fused_cta_kernel": 2749092147},
+    #   fused_kernel: 1240935.5 KiB fetched, 39843.3 KiB written
+    #   fused_cta_kernel: 1322148.0 KiB fetched, 40364.3 KiB written
 }
 
 
