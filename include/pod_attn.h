@@ -83,7 +83,7 @@ typedef enum {
  * rounding (the decode kernel adds its weights in another order).  Built for head_dim 128 and for
  * contiguous caches or paged ones with power-of-two blocks of at least 16 tokens; otherwise
  * POD_ERR_UNSUPPORTED.  Not chosen automatically: on this chip it ends a prefill-heavy batch
- * 3-8 % sooner when launches are spaced out and 0-2.5 % sooner in a sustained loop, where the chip
+ * 3-8 % sooner when launches are spaced out and 1-3 % sooner in a sustained loop, where the chip
  * clocks down under the power the two kernels draw together, and is slower on decode-bound batches.
  * Also accepted with POD_MODE_PREFILL_ONLY and POD_MODE_DECODE_ONLY, which then run that
  * configuration's prefill or decode kernel alone.  Like POD_MODE_STREAMS it creates streams and
